@@ -1,0 +1,188 @@
+/*
+ * qmm.h -- C ABI of the MI355X (gfx950) quantized-matmul library.
+ *
+ * The library implements the hot path of "A Metric Driven Approach to Mixed
+ * Precision Training" (arXiv 2408.02897): for one matrix multiply,
+ *   qmm_scale     step size delta = max|X| / qmax per scale group   (Eq. 1, right half)
+ *   qmm_quantize  codes = round(X / delta) onto INT8 / E4M3 / E5M2  (Eq. 1, left half;
+ *                 Methodology bullets on saturation, underflow and rounding)
+ *   qmm_gemm      8-bit x 8-bit product in a wide accumulator, then
+ *                 descale by deltaL * deltaR                        (Methodology, scaling bullet)
+ *   qmm_metric    error sums of the result against the high-precision
+ *                 product: noise-to-signal ratio, Eq. 2, Eq. 3      (Results, Eq. 2 and Eq. 3)
+ *
+ * General rules
+ *  - Every pointer named "device" is GPU memory owned by the caller; the
+ *    library allocates nothing, keeps no state between calls and frees nothing.
+ *    Descriptor structs (qmm_tensor, qmm_operand, qmm_granularity) are host memory
+ *    and are read before the call returns.
+ *  - Calls validate their arguments on the host, enqueue kernels on `stream`
+ *    (a hipStream_t passed as void*; NULL = the default stream) and return
+ *    without synchronising.  Results stay on the device.
+ *  - Argument errors are reported before anything is launched and leave the
+ *    outputs untouched.  A launch failure returns QMM_ERR_LAUNCH.
+ *  - NaN / inf inputs and all-zero groups are not errors; their results are
+ *    defined below.
+ *  - Arithmetic is IEEE binary32 unless stated, round-to-nearest-even,
+ *    subnormals kept.
+ *
+ * Scale groups.  A tensor is a batch of matrices [batch][rows][cols].  Matrix b
+ * belongs to batch group g = b % batch_groups (batch_groups = 1: one group for
+ * the whole batch, "tensor"/"channel" level; batch_groups = H with the batch
+ * laid out [example][head]: one group per head, shared by the examples).  With
+ * per_channel = 1 every index c of the non-contracting axis has its own step
+ * size, shared by the matrices of the group: delta[g * C + c], C = extent of
+ * the non-contracting axis.  With per_channel = 0: delta[g].
+ */
+#ifndef QMM_H
+#define QMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QMM_OK = 0,
+    QMM_ERR_NULL = 1,        /* a required pointer is NULL                        */
+    QMM_ERR_SHAPE = 2,       /* negative extent, stride smaller than extent, ...  */
+    QMM_ERR_ENUM = 3,        /* unknown format / dtype / rounding / axis value    */
+    QMM_ERR_ALIGN = 4,       /* pointer or extent alignment rule violated         */
+    QMM_ERR_UNSUPPORTED = 5, /* valid request this build does not implement       */
+    QMM_ERR_WORKSPACE = 6,   /* workspace missing or too small                    */
+    QMM_ERR_LAUNCH = 7       /* the HIP runtime refused a launch                  */
+} qmm_status;
+
+/* 8-bit formats of the paper, plus the un-quantized pass-through used for the
+ * high-precision reference product.  Largest magnitudes: 127, 448, 57344. */
+typedef enum { QMM_FMT_INT8 = 0, QMM_FMT_E4M3 = 1, QMM_FMT_E5M2 = 2, QMM_FMT_BF16 = 3 } qmm_format;
+typedef enum { QMM_DT_BF16 = 0, QMM_DT_F32 = 1 } qmm_dtype;
+typedef enum { QMM_ROUND_RTNE = 0, QMM_ROUND_STOCHASTIC = 1 } qmm_round;
+
+/* A batch of row-major matrices in device memory.  Element (b, r, c) is at
+ * data[b*batch_stride + r*row_stride + c] (strides in elements, columns are
+ * contiguous).  contract_axis names the axis the matrix multiply sums over:
+ * 1 = columns (an [M][K] operand), 0 = rows (a [K][M] operand, e.g. the
+ * activations and the upstream gradient in a weight-gradient product). */
+typedef struct {
+    const void* data;        /* device */
+    int32_t dtype;           /* qmm_dtype */
+    int32_t contract_axis;   /* 0 or 1 */
+    int64_t batch, rows, cols;
+    int64_t batch_stride, row_stride;
+} qmm_tensor;
+
+typedef struct {
+    int32_t per_channel;     /* 0: one step size per batch group; 1: one per non-contracting index */
+    int32_t reserved;        /* must be 0 */
+    int64_t batch_groups;    /* >= 1 and dividing nothing in particular: group = b % batch_groups  */
+} qmm_granularity;
+
+/* Number of step sizes qmm_scale writes / qmm_quantize reads for this tensor. */
+int64_t qmm_num_scales(const qmm_tensor* x, const qmm_granularity* g);
+
+/*
+ * Step 1 -- step size (Eq. 1: delta = max|X| / (2^(n-1)-1); for FP8 the
+ * denominator is the format maximum, last Methodology bullet).
+ *   delta_out  device, qmm_num_scales() floats.
+ *   workspace  device scratch of at least qmm_scale_workspace_size() bytes,
+ *              16-byte aligned; contents on entry are irrelevant.
+ * Defined results: the maximum is taken over magnitude bit patterns, so an
+ * inf or NaN element makes its group's delta inf / NaN; an all-zero (or
+ * empty) group gets delta = 1; a quotient below 2^-126 is raised to 2^-126.
+ * fmt must be one of the three 8-bit formats.
+ */
+size_t qmm_scale_workspace_size(const qmm_tensor* x, const qmm_granularity* g);
+qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g,
+                     float* delta_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Step 2 -- quantize (Eq. 1: code = round(X / delta)).  The quotient is formed
+ * as t = fl(x * fl(1/delta)): one correctly rounded reciprocal per group, one
+ * correctly rounded product per element.
+ *   INT8: round half to even, keep [-127, 127], two's complement byte; NaN -> 0.
+ *   E4M3 / E5M2 (OCP FP8 value sets): nearest finite value, ties to the even
+ *   mantissa, |t| above the maximum (and inf) -> +-maximum, sign of t kept
+ *   (negative underflow -> 0x80), NaN -> 0x7F.
+ *   QMM_ROUND_STOCHASTIC: with lo <= |t| < hi the neighbouring grid values, the
+ *   result is hi iff u < (|t|-lo)/(hi-lo), u = (24 random bits)/2^24.  The bits
+ *   of output element p (linear index in codes_out) are the top 24 bits of word
+ *   (p+offset)%4 of Philox4x32-10 with counter ((p+offset)/4, 0) as two 32-bit
+ *   halves followed by two zero words, and key = seed as two 32-bit halves, so
+ *   a tensor quantized in pieces with matching offsets equals the whole.
+ *   codes_out  device, [batch][non-contracting][contracting] bytes, dense: the
+ *              contracting axis is contiguous whatever contract_axis is.
+ *   delta      device, as written by qmm_scale (or supplied by the caller).
+ * Uses no workspace.
+ */
+qmm_status qmm_quantize(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g,
+                        const float* delta, qmm_round mode, uint64_t seed, uint64_t offset,
+                        uint8_t* codes_out, void* stream);
+
+/* One operand of qmm_gemm: a dense batch [batch][rows][K] with K contiguous. */
+typedef struct {
+    const void* data;        /* device; 8-bit codes, or bfloat16 values (see is_codes)          */
+    int32_t format;          /* qmm_format the operand is multiplied in                          */
+    int32_t is_codes;        /* 1: data holds 8-bit codes of `format`.
+                                0: data holds bfloat16; with an 8-bit `format` the values are
+                                   quantized with `delta` (RTNE) while they are staged for the
+                                   multiply; with QMM_FMT_BF16 they are multiplied as they are. */
+    const float* delta;      /* device step sizes (ignored for QMM_FMT_BF16)                     */
+    qmm_granularity gran;    /* how delta is indexed; per_channel refers to the operand's rows   */
+} qmm_operand;
+
+/*
+ * Steps 3 and 4 -- Y[b][i][j] = (acc * deltaA[i]) * deltaB[j],
+ * acc = sum_k value(A[b][i][k]) * value(B[b][j][k])   (third Methodology bullet:
+ * scaling before and after the multiply, result held in a wider accumulator).
+ *   INT8 x INT8 accumulates exactly in int32 (|acc| must stay below 2^31);
+ *   FP8 x FP8 (E4M3 and E5M2 may be mixed) accumulates in binary32; the
+ *   summation order is unspecified;  BF16 x BF16 accumulates in binary32 and
+ *   is not descaled (the high-precision reference product).
+ *   Both operands must be 8-bit formats of the same family (both INT8 or both
+ *   FP8) or both BF16.  INT8 code 0x80 (-128) is outside the format: undefined.
+ *   y          device [batch][M][N], y_dtype F32 or BF16 (RNE).  May be NULL if
+ *              acc_out is given.
+ *   acc_out    device [batch][M][N] raw accumulators (int32 for INT8, else
+ *              binary32) or NULL.
+ *   K must be a multiple of 16 bytes' worth of elements (16 codes / 8 bf16)
+ *   and all data pointers 16-byte aligned, else QMM_ERR_ALIGN.
+ *   workspace  device scratch of at least qmm_gemm_workspace_size() bytes
+ *              (may be 0, then NULL is accepted).
+ */
+size_t qmm_gemm_workspace_size(const qmm_operand* a, const qmm_operand* b,
+                               int64_t batch, int64_t M, int64_t N, int64_t K);
+qmm_status qmm_gemm(const qmm_operand* a, const qmm_operand* b,
+                    int64_t batch, int64_t M, int64_t N, int64_t K,
+                    void* y, qmm_dtype y_dtype, void* acc_out,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Step 6 -- error metrics of y against the high-precision result y_ref, one
+ * pass, binary64 accumulation, e = y - y_ref.  out16 (device, 16 doubles):
+ *   [0] sum e^2          [1] sum ref^2        (noise-to-signal ratio = [0]/[1])
+ *   [2] sum |e|          [3] sum |ref|
+ *   [4] max |e|          [5] max |ref|
+ *   [6] sum over ref != 0 of |e|/|ref|   [7] its max   [8] its term count   (Eq. 2)
+ *   [9] sum over d > 0 of |e|/d          [10] its max  [11] its term count  (Eq. 3, element-wise;
+ *        d = (|L|.|R|)_ij supplied by the caller in denom, or NULL: [9..11] = 0)
+ *   [12] elements counted   [13] elements skipped because e is NaN   [14],[15] = 0
+ * Elements whose error is NaN are left out of every sum and maximum.
+ *   y          device, n elements of y_dtype;  y_ref, denom: device, n floats.
+ *   workspace  device scratch, qmm_metric_workspace_size(n) bytes, 16-byte aligned.
+ * n = 0 writes sixteen zeros.
+ */
+size_t qmm_metric_workspace_size(int64_t n);
+qmm_status qmm_metric(const void* y, qmm_dtype y_dtype, const float* y_ref, const float* denom,
+                      int64_t n, double* out16, void* workspace, size_t workspace_bytes, void* stream);
+
+const char* qmm_status_string(qmm_status s);
+/* Version of this ABI (major*100 + minor). */
+int qmm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QMM_H */

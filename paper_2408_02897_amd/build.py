@@ -1,0 +1,42 @@
+"""Build libqmm.so (HIP, gfx950 only) in-tree with hipcc.
+
+    python -m paper_2408_02897_amd.build [--force]
+"""
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+OBJDIR = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libqmm.so")
+SOURCES = ["qmm_api.hip", "qmm_scale.hip", "qmm_quantize.hip", "qmm_metric.hip", "qmm_gemm.hip"]
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+
+def _compile(src, force):
+    obj = os.path.join(OBJDIR, src.replace(".hip", ".o"))
+    path = os.path.join(CSRC, src)
+    deps = [path, os.path.join(CSRC, "qmm_device.h"), os.path.join(ROOT, "include", "qmm.h")]
+    if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
+        return obj
+    subprocess.run([HIPCC, *FLAGS, "-c", path, "-o", obj], check=True)
+    return obj
+
+
+def build(force=False):
+    os.makedirs(OBJDIR, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=5) as ex:
+        objs = list(ex.map(lambda s: _compile(s, force), SOURCES))
+    if force or not os.path.exists(LIB) or any(os.path.getmtime(o) > os.path.getmtime(LIB) for o in objs):
+        subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force="--force" in sys.argv))

@@ -1,0 +1,184 @@
+// qmm_metric: one pass over (y, y_ref[, denom]) accumulating in binary64 the
+// sums behind the noise-to-signal ratio, the relative error of Eq. 2 and the
+// element-wise backward error of Eq. 3.  HBM-bound: 8 B per element for a
+// binary32 y (6 B for bfloat16 y, +4 B with denominators).  Every thread keeps
+// private sums, wavefronts fold them by shuffles, workgroups through LDS, and a
+// one-workgroup second kernel folds the per-workgroup partials in a fixed order:
+// no atomics, so the result is reproducible run to run.
+#include "qmm_device.h"
+
+namespace qmm {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxBlocks = 2048;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+struct Acc {
+    double s_ee = 0, s_rr = 0, s_ae = 0, s_ar = 0, m_e = 0, m_r = 0;
+    double re_sum = 0, re_max = 0, be_sum = 0, be_max = 0;
+    unsigned long long re_cnt = 0, be_cnt = 0, n = 0, nan_cnt = 0;
+
+    template <bool HAS_D> QMM_DEV void add(float yf, float rf, float df)
+    {
+        const double e = (double)yf - (double)rf;
+        if (e != e) { ++nan_cnt; return; }
+        const double ae = fabs(e), ar = fabs((double)rf);
+        s_ee = fma(e, e, s_ee);
+        s_rr = fma(ar, ar, s_rr);
+        s_ae += ae;
+        s_ar += ar;
+        m_e = fmax(m_e, ae);
+        m_r = fmax(m_r, ar);
+        if (ar != 0.0) {
+            const double q = ae / ar;
+            re_sum += q;
+            re_max = fmax(re_max, q);
+            ++re_cnt;
+        }
+        if constexpr (HAS_D) {
+            const double d = (double)df;
+            if (d > 0.0) {
+                const double q = ae / d;
+                be_sum += q;
+                be_max = fmax(be_max, q);
+                ++be_cnt;
+            }
+        }
+        ++n;
+    }
+};
+
+// Products e*e and ar*ar are exact in binary64 (24-bit x 24-bit and the error of two binary32 values
+// has at most 49 significant bits... e*e may round); fma keeps one rounding per term, as a plain
+// multiply-then-add would have two.  Either way the comparison tolerance covers it.
+
+QMM_DEV void store_partial(const Acc& a, double* out)
+{
+    __shared__ double s[kThreads / kWave][16];
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+    double v[16];
+    v[0] = wave_sum_f64(a.s_ee); v[1] = wave_sum_f64(a.s_rr); v[2] = wave_sum_f64(a.s_ae); v[3] = wave_sum_f64(a.s_ar);
+    v[4] = wave_max_f64(a.m_e); v[5] = wave_max_f64(a.m_r);
+    v[6] = wave_sum_f64(a.re_sum); v[7] = wave_max_f64(a.re_max); v[8] = wave_sum_f64((double)a.re_cnt);
+    v[9] = wave_sum_f64(a.be_sum); v[10] = wave_max_f64(a.be_max); v[11] = wave_sum_f64((double)a.be_cnt);
+    v[12] = wave_sum_f64((double)a.n); v[13] = wave_sum_f64((double)a.nan_cnt);
+    v[14] = 0.0; v[15] = 0.0;
+    if (lane == 0) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[w][i] = v[i];
+    }
+    __syncthreads();
+    if (threadIdx.x < 16) {
+        const int i = threadIdx.x;
+        const bool is_max = (i == 4 || i == 5 || i == 7 || i == 10);
+        double r = s[0][i];
+        for (int k = 1; k < kThreads / kWave; ++k) r = is_max ? fmax(r, s[k][i]) : r + s[k][i];
+        out[i] = r;
+    }
+}
+
+template <bool Y_BF16, bool HAS_D> __global__ void __launch_bounds__(kThreads)
+metric_partial(const void* __restrict__ yv, const float* __restrict__ r, const float* __restrict__ d, int64_t n,
+               double* __restrict__ partial)
+{
+    Acc acc;
+    const int64_t nvec = n >> 2;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    const int64_t tid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const f32x4* r4 = reinterpret_cast<const f32x4*>(r);
+    const f32x4* d4 = reinterpret_cast<const f32x4*>(d);
+    for (int64_t i = tid; i < nvec; i += stride) {
+        f32x4 y;
+        if constexpr (Y_BF16) {
+            const u32x2 w = reinterpret_cast<const u32x2*>(yv)[i];
+            y = f32x4{__uint_as_float(w[0] << 16), __uint_as_float(w[0] & 0xFFFF0000u),
+                      __uint_as_float(w[1] << 16), __uint_as_float(w[1] & 0xFFFF0000u)};
+        } else {
+            y = reinterpret_cast<const f32x4*>(yv)[i];
+        }
+        const f32x4 rr = r4[i];
+        f32x4 dd = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (HAS_D) dd = d4[i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc.add<HAS_D>(y[j], rr[j], dd[j]);
+    }
+    // tail elements (n % 4), one thread each
+    const int64_t t = (nvec << 2) + tid;
+    if (t < n) {
+        float y;
+        if constexpr (Y_BF16) y = bf16_bits_to_f32(static_cast<const uint16_t*>(yv)[t]);
+        else y = static_cast<const float*>(yv)[t];
+        acc.add<HAS_D>(y, r[t], HAS_D ? d[t] : 0.f);
+    }
+    store_partial(acc, partial + (int64_t)blockIdx.x * 16);
+}
+
+__global__ void __launch_bounds__(kThreads)
+metric_finalize(const double* __restrict__ partial, int nblocks, double* __restrict__ out)
+{
+    // thread i < 16 folds field i over the workgroups in ascending order (fixed order => reproducible);
+    // the other threads of the workgroup idle: nblocks <= 2048 doubles per field.
+    __shared__ double s[16][kThreads / 16];
+    const int field = threadIdx.x & 15, part = threadIdx.x >> 4;   // 16 fields x 16 strided parts
+    const bool is_max = (field == 4 || field == 5 || field == 7 || field == 10);
+    double r = 0.0;
+    for (int b = part; b < nblocks; b += kThreads / 16) {
+        const double v = partial[(int64_t)b * 16 + field];
+        r = is_max ? fmax(r, v) : r + v;
+    }
+    s[field][part] = r;
+    __syncthreads();
+    if (threadIdx.x < 16) {
+        double t = s[threadIdx.x][0];
+        const bool mx = (threadIdx.x == 4 || threadIdx.x == 5 || threadIdx.x == 7 || threadIdx.x == 10);
+        for (int k = 1; k < kThreads / 16; ++k) t = mx ? fmax(t, s[threadIdx.x][k]) : t + s[threadIdx.x][k];
+        out[threadIdx.x] = t;
+    }
+}
+
+int plan_blocks(int64_t n)
+{
+    const int64_t per_block = (int64_t)kThreads * 4 * 4;   // four 4-element vectors per thread at least
+    int64_t nb = (n + per_block - 1) / per_block;
+    if (nb < 1) nb = 1;
+    if (nb > kMaxBlocks) nb = kMaxBlocks;
+    return (int)nb;
+}
+
+}  // namespace
+}  // namespace qmm
+
+using namespace qmm;
+
+extern "C" size_t qmm_metric_workspace_size(int64_t n)
+{
+    return (size_t)plan_blocks(n < 0 ? 0 : n) * 16 * sizeof(double);
+}
+
+extern "C" qmm_status qmm_metric(const void* y, qmm_dtype y_dtype, const float* y_ref, const float* denom, int64_t n,
+                                 double* out16, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!out16) return QMM_ERR_NULL;
+    if (y_dtype != QMM_DT_BF16 && y_dtype != QMM_DT_F32) return QMM_ERR_ENUM;
+    if (n < 0) return QMM_ERR_SHAPE;
+    if (n > 0 && (!y || !y_ref)) return QMM_ERR_NULL;
+    if (!workspace || workspace_bytes < qmm_metric_workspace_size(n)) return QMM_ERR_WORKSPACE;
+    if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(out16) & 7u)) return QMM_ERR_ALIGN;
+    if (n > 0 && (!aligned16(y_ref) || (denom && !aligned16(denom)) ||
+                  (reinterpret_cast<uintptr_t>(y) & (y_dtype == QMM_DT_BF16 ? 7u : 15u))))
+        return QMM_ERR_ALIGN;
+
+    hipStream_t s = as_stream(stream);
+    double* partial = static_cast<double*>(workspace);
+    const int nb = plan_blocks(n);
+    const bool bf = y_dtype == QMM_DT_BF16, hd = denom != nullptr;
+    if (bf && hd) metric_partial<true, true><<<nb, kThreads, 0, s>>>(y, y_ref, denom, n, partial);
+    else if (bf) metric_partial<true, false><<<nb, kThreads, 0, s>>>(y, y_ref, denom, n, partial);
+    else if (hd) metric_partial<false, true><<<nb, kThreads, 0, s>>>(y, y_ref, denom, n, partial);
+    else metric_partial<false, false><<<nb, kThreads, 0, s>>>(y, y_ref, denom, n, partial);
+    if (hipGetLastError() != hipSuccess) return QMM_ERR_LAUNCH;
+    metric_finalize<<<1, kThreads, 0, s>>>(partial, nb, out16);
+    return launch_status();
+}

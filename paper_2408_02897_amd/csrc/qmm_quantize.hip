@@ -1,0 +1,214 @@
+// qmm_quantize: codes = round(X / delta) onto INT8 / E4M3 / E5M2 (Eq. 1, left
+// half; Methodology bullets on saturation, underflow and the two rounding
+// modes).  HBM-bound: 2 B read + 1 B written per bfloat16 element.  The quotient
+// is x * (1/delta) with one IEEE reciprocal per thread-row and one product per
+// element.  Codes are written with the contracting axis contiguous; when the
+// input contracts over its rows the tile is transposed through LDS.
+#include "qmm_device.h"
+
+namespace qmm {
+namespace {
+
+constexpr int kThreads = 256;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+struct QArgs {
+    const void* x;
+    const float* delta;
+    uint8_t* codes;
+    int64_t batch, rows, cols, batch_stride, row_stride;
+    int64_t groups;        // batch groups
+    int64_t channels;      // step sizes per group (1 when not per-channel)
+    uint64_t seed, offset;
+};
+
+template <typename T> QMM_DEV float load_f32(const T* p);
+template <> QMM_DEV float load_f32<uint16_t>(const uint16_t* p) { return bf16_bits_to_f32(*p); }
+template <> QMM_DEV float load_f32<float>(const float* p) { return *p; }
+
+// Row-contracting fast path: bfloat16, cols % 16 == 0, 16-byte aligned rows.  One thread = 16 consecutive
+// elements of a row: two 16-byte loads, one 16-byte store.  grid (ceil(rows*cols/16 / 256), batch).
+template <int FMT, int MODE> __global__ void __launch_bounds__(kThreads)
+quantize_rows_bf16x16(QArgs a)
+{
+    const int64_t vpr = a.cols >> 4;
+    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (v >= vpr * a.rows) return;
+    const int64_t b = blockIdx.y;
+    const int64_t r = v / vpr, cv = v - r * vpr;
+    const float d = a.delta[(b % a.groups) * a.channels + (a.channels > 1 ? r : 0)];
+    const float rho = 1.0f / d;
+    const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.x) + b * a.batch_stride +
+                                                      r * a.row_stride + cv * 16);
+    const u32x4 w0 = src[0], w1 = src[1];
+    const int64_t p0 = (b * a.rows + r) * a.cols + cv * 16;
+    SrStream sr(a.seed);
+    u32x4 out;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t packed = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = q * 4 + j;
+            const uint32_t word = e < 8 ? w0[e >> 1] : w1[(e - 8) >> 1];
+            const float xv = (e & 1) ? __uint_as_float(word & 0xFFFF0000u) : __uint_as_float(word << 16);
+            const float t = xv * rho;
+            uint32_t u24 = 0;
+            if constexpr (MODE == QMM_ROUND_STOCHASTIC) u24 = sr.bits((uint64_t)(p0 + e) + a.offset);
+            packed |= encode<FMT, MODE>(t, u24) << (8 * j);
+        }
+        out[q] = packed;
+    }
+    *reinterpret_cast<u32x4*>(a.codes + p0) = out;
+}
+
+// Generic path: one thread per output code, any dtype / stride / contracting axis.
+template <typename T, int FMT, int MODE> __global__ void __launch_bounds__(kThreads)
+quantize_generic(QArgs a, int contract_axis)
+{
+    const int64_t NC = contract_axis == 1 ? a.rows : a.cols;
+    const int64_t KC = contract_axis == 1 ? a.cols : a.rows;
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= NC * KC) return;
+    const int64_t b = blockIdx.y;
+    const int64_t n = i / KC, k = i - n * KC;
+    const int64_t r = contract_axis == 1 ? n : k, c = contract_axis == 1 ? k : n;
+    const float d = a.delta[(b % a.groups) * a.channels + (a.channels > 1 ? n : 0)];
+    const float rho = 1.0f / d;
+    const float t = load_f32<T>(static_cast<const T*>(a.x) + b * a.batch_stride + r * a.row_stride + c) * rho;
+    const int64_t p = (b * NC + n) * KC + k;
+    uint32_t u24 = 0;
+    if constexpr (MODE == QMM_ROUND_STOCHASTIC) {
+        SrStream sr(a.seed);
+        u24 = sr.bits((uint64_t)p + a.offset);
+    }
+    a.codes[p] = (uint8_t)encode<FMT, MODE>(t, u24);
+}
+
+// Column-contracting fast path (the input is [K][N], codes are [N][K]): bfloat16, rows % 16 == 0 is NOT
+// required; cols % 8 == 0 and 16-byte aligned rows are.  Workgroup tile = 128 k x 128 n.  Thread (tn, tk)
+// loads 8 rows (k) x 8 columns (n) as eight 16-byte vectors, packs the 8 codes of each column into two
+// dwords and parks them in an LDS tile [n][k]; then every thread writes 16-byte pieces of finished code
+// rows, 128 contiguous bytes per n.  grid (ceil(cols/128), ceil(rows/128), batch).
+constexpr int kTile = 128;
+constexpr int kTileRowBytes = kTile + 16;   // padded row of the LDS code tile
+
+template <int FMT, int MODE> __global__ void __launch_bounds__(kThreads)
+quantize_cols_bf16(QArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t tile[kTile * kTileRowBytes];
+    const int tn = threadIdx.x & 15, tk = threadIdx.x >> 4;
+    const int64_t b = blockIdx.z;
+    const int64_t n0 = (int64_t)blockIdx.x * kTile, k0 = (int64_t)blockIdx.y * kTile;
+    const int64_t K = a.rows, N = a.cols;
+    const int64_t n = n0 + tn * 8;
+    const uint16_t* base = static_cast<const uint16_t*>(a.x) + b * a.batch_stride;
+    float rho[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int64_t nn = n + j < N ? n + j : N - 1;
+        rho[j] = 1.0f / a.delta[(b % a.groups) * a.channels + (a.channels > 1 ? nn : 0)];
+    }
+    uint32_t lo[8] = {}, hi[8] = {};
+    SrStream sr(a.seed);
+    if (n < N) {
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            const int64_t k = k0 + tk * 8 + kk;
+            u32x4 w = {0u, 0u, 0u, 0u};
+            if (k < K) w = *reinterpret_cast<const u32x4*>(base + k * a.row_stride + n);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t word = w[j >> 1];
+                const float xv = (j & 1) ? __uint_as_float(word & 0xFFFF0000u) : __uint_as_float(word << 16);
+                const float t = xv * rho[j];
+                uint32_t u24 = 0;
+                if constexpr (MODE == QMM_ROUND_STOCHASTIC)
+                    u24 = sr.bits((uint64_t)((b * N + n + j) * K + k) + a.offset);
+                const uint32_t code = encode<FMT, MODE>(t, u24);
+                if (kk < 4) lo[j] |= code << (8 * kk); else hi[j] |= code << (8 * (kk - 4));
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        u32x2 v = {lo[j], hi[j]};
+        *reinterpret_cast<u32x2*>(&tile[(tn * 8 + j) * kTileRowBytes + tk * 8]) = v;
+    }
+    __syncthreads();
+    // 128 code rows x 8 pieces of 16 bytes = 1024 pieces, 4 per thread
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int piece = it * kThreads + threadIdx.x;
+        const int row = piece >> 3, seg = piece & 7;
+        const int64_t nn = n0 + row, kk = k0 + seg * 16;
+        if (nn >= N || kk >= K) continue;
+        uint8_t* dst = a.codes + (b * N + nn) * K + kk;
+        const uint8_t* srcp = &tile[row * kTileRowBytes + seg * 16];
+        if (kk + 16 <= K && (K & 15) == 0) {
+            *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(srcp);
+        } else {
+            for (int e = 0; e < 16 && kk + e < K; ++e) dst[e] = srcp[e];
+        }
+    }
+}
+
+template <int FMT, int MODE> qmm_status launch(const qmm_tensor* x, const QArgs& a, hipStream_t s)
+{
+    const bool bf16 = x->dtype == QMM_DT_BF16;
+    const bool aligned = aligned16(x->data) && (x->row_stride % 8 == 0) && (x->batch_stride % 8 == 0);
+    if (bf16 && aligned && x->contract_axis == 1 && (x->cols % 16 == 0) && aligned16(a.codes)) {
+        const int64_t nv = x->rows * (x->cols / 16);
+        quantize_rows_bf16x16<FMT, MODE><<<dim3((unsigned)((nv + kThreads - 1) / kThreads), (unsigned)x->batch), kThreads, 0, s>>>(a);
+    } else if (bf16 && aligned && x->contract_axis == 0 && (x->cols % 8 == 0) && aligned16(a.codes)) {
+        quantize_cols_bf16<FMT, MODE><<<dim3((unsigned)((x->cols + kTile - 1) / kTile), (unsigned)((x->rows + kTile - 1) / kTile),
+                                              (unsigned)x->batch), kThreads, 0, s>>>(a);
+    } else {
+        const int64_t n = x->rows * x->cols;
+        const dim3 grid((unsigned)((n + kThreads - 1) / kThreads), (unsigned)x->batch);
+        if (bf16) quantize_generic<uint16_t, FMT, MODE><<<grid, kThreads, 0, s>>>(a, x->contract_axis);
+        else quantize_generic<float, FMT, MODE><<<grid, kThreads, 0, s>>>(a, x->contract_axis);
+    }
+    return launch_status();
+}
+
+template <int FMT> qmm_status launch_mode(const qmm_tensor* x, const QArgs& a, qmm_round mode, hipStream_t s)
+{
+    return mode == QMM_ROUND_RTNE ? launch<FMT, QMM_ROUND_RTNE>(x, a, s) : launch<FMT, QMM_ROUND_STOCHASTIC>(x, a, s);
+}
+
+}  // namespace
+}  // namespace qmm
+
+using namespace qmm;
+
+extern "C" qmm_status qmm_quantize(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g, const float* delta,
+                                   qmm_round mode, uint64_t seed, uint64_t offset, uint8_t* codes_out, void* stream)
+{
+    if (!x || !g) return QMM_ERR_NULL;
+    if (x->dtype != QMM_DT_BF16 && x->dtype != QMM_DT_F32) return QMM_ERR_ENUM;
+    if (x->contract_axis != 0 && x->contract_axis != 1) return QMM_ERR_ENUM;
+    if (fmt != QMM_FMT_INT8 && fmt != QMM_FMT_E4M3 && fmt != QMM_FMT_E5M2) return QMM_ERR_ENUM;
+    if (mode != QMM_ROUND_RTNE && mode != QMM_ROUND_STOCHASTIC) return QMM_ERR_ENUM;
+    if (g->batch_groups < 1 || g->reserved != 0 || (g->per_channel != 0 && g->per_channel != 1)) return QMM_ERR_ENUM;
+    if (x->batch < 0 || x->rows < 0 || x->cols < 0 || x->row_stride < x->cols) return QMM_ERR_SHAPE;
+    if (x->batch > 1 && x->rows > 0 && x->batch_stride < (x->rows - 1) * x->row_stride + x->cols) return QMM_ERR_SHAPE;
+    if (x->batch > 65535) return QMM_ERR_UNSUPPORTED;
+    if (x->batch * x->rows * x->cols == 0) return QMM_OK;
+    if (!x->data || !delta || !codes_out) return QMM_ERR_NULL;
+
+    QArgs a;
+    a.x = x->data; a.delta = delta; a.codes = codes_out;
+    a.batch = x->batch; a.rows = x->rows; a.cols = x->cols;
+    a.batch_stride = x->batch_stride; a.row_stride = x->row_stride;
+    a.groups = g->batch_groups;
+    a.channels = g->per_channel ? (x->contract_axis == 1 ? x->rows : x->cols) : 1;
+    a.seed = seed; a.offset = offset;
+    hipStream_t s = as_stream(stream);
+    switch (fmt) {
+    case QMM_FMT_INT8: return launch_mode<QMM_FMT_INT8>(x, a, mode, s);
+    case QMM_FMT_E4M3: return launch_mode<QMM_FMT_E4M3>(x, a, mode, s);
+    default: return launch_mode<QMM_FMT_E5M2>(x, a, mode, s);
+    }
+}

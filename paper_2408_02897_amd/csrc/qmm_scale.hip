@@ -1,0 +1,313 @@
+// qmm_scale: step size delta = max|X| / qmax per scale group (Eq. 1, right half;
+// Methodology bullets on scale granularity and on aligning the absmax with the
+// format maximum).  HBM-bound: every element is read once (2 B for bfloat16),
+// the maximum is taken on magnitude bit patterns (exact, order-free), partial
+// maxima go to the workspace and a second small kernel folds them per group
+// and does the one division.  Two phases, no atomics, so the result does not
+// depend on launch geometry.
+#include "qmm_device.h"
+
+namespace qmm {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxFlatBlocks = 2048;   // 8 workgroups per CU on 256 CUs
+constexpr int kColSlabRows = 256;      // rows folded by one workgroup in the column-group kernel
+
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+QMM_DEV uint32_t block_max_u32(uint32_t v)
+{
+    __shared__ uint32_t s[kThreads / kWave];
+    v = wave_max_u32(v);
+    if ((threadIdx.x & (kWave - 1)) == 0) s[threadIdx.x / kWave] = v;
+    __syncthreads();
+    uint32_t r = s[0];
+#pragma unroll
+    for (int i = 1; i < kThreads / kWave; ++i) r = max(r, s[i]);
+    return r;
+}
+
+// 8 bfloat16 magnitudes packed in a 16-byte vector -> running packed maxima.
+QMM_DEV void fold_bf16x8(u32x4 w, u16x2 (&m)[4])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t a = w[i] & 0x7FFF7FFFu;
+        m[i] = __builtin_elementwise_max(m[i], __builtin_bit_cast(u16x2, a));
+    }
+}
+QMM_DEV uint32_t finish_bf16(const u16x2 (&m)[4])
+{
+    uint32_t r = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r = max(r, max((uint32_t)m[i][0], (uint32_t)m[i][1]));
+    return r << 16;   // bfloat16 magnitude -> binary32 magnitude bits
+}
+
+// Dense matrix (row_stride == cols), bfloat16, 16-byte vectors: grid (nblk, batch).
+__global__ void __launch_bounds__(kThreads)
+absmax_flat_bf16(const uint16_t* __restrict__ x, int64_t batch_stride, int64_t nvec, uint32_t* __restrict__ partial)
+{
+    const u32x4* p = reinterpret_cast<const u32x4*>(x + (int64_t)blockIdx.y * batch_stride);
+    u16x2 m[4] = {};
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    for (; i + 3 * stride < nvec; i += 4 * stride) {
+        const u32x4 a = p[i], b = p[i + stride];
+        const u32x4 c = p[i + 2 * stride], d = p[i + 3 * stride];
+        fold_bf16x8(a, m); fold_bf16x8(b, m); fold_bf16x8(c, m); fold_bf16x8(d, m);
+    }
+    for (; i < nvec; i += stride) fold_bf16x8(p[i], m);
+    const uint32_t r = block_max_u32(finish_bf16(m));
+    if (threadIdx.x == 0) partial[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = r;
+}
+
+template <typename T> QMM_DEV uint32_t mag_bits(T v);
+template <> QMM_DEV uint32_t mag_bits<uint16_t>(uint16_t v) { return ((uint32_t)v & 0x7FFFu) << 16; }
+template <> QMM_DEV uint32_t mag_bits<float>(float v) { return __float_as_uint(v) & 0x7FFFFFFFu; }
+
+// One wavefront per (matrix, row): partial[b*rows + r] = absmax of the row.  Any stride, any dtype.
+template <typename T> __global__ void __launch_bounds__(kThreads)
+absmax_rows(const T* __restrict__ x, int64_t batch_stride, int64_t row_stride, int64_t rows, int64_t cols,
+            int64_t total_rows, uint32_t* __restrict__ partial)
+{
+    const int64_t wr = (int64_t)blockIdx.x * (kThreads / kWave) + threadIdx.x / kWave;
+    if (wr >= total_rows) return;
+    const int64_t b = wr / rows, r = wr % rows;
+    const T* p = x + b * batch_stride + r * row_stride;
+    const int lane = threadIdx.x & (kWave - 1);
+    uint32_t m = 0;
+    if constexpr (sizeof(T) == 2) {
+        if ((cols & 7) == 0 && (reinterpret_cast<uintptr_t>(p) & 15u) == 0) {
+            const u32x4* pv = reinterpret_cast<const u32x4*>(p);
+            u16x2 mm[4] = {};
+            for (int64_t i = lane; i < cols / 8; i += kWave) fold_bf16x8(pv[i], mm);
+            m = finish_bf16(mm);
+        } else {
+            for (int64_t i = lane; i < cols; i += kWave) m = max(m, mag_bits<T>(p[i]));
+        }
+    } else {
+        for (int64_t i = lane; i < cols; i += kWave) m = max(m, mag_bits<T>(p[i]));
+    }
+    m = wave_max_u32(m);
+    if (lane == 0) partial[wr] = m;
+}
+
+// Column groups: workgroup = 32 column-vectors (256 columns) x 8 row lanes over a slab of rows.
+// partial[(b*nslab + slab)*cols + c].  bfloat16, cols % 8 == 0, 16-byte aligned rows.
+__global__ void __launch_bounds__(kThreads)
+absmax_cols_bf16(const uint16_t* __restrict__ x, int64_t batch_stride, int64_t row_stride, int64_t rows, int64_t cols,
+                 uint32_t* __restrict__ partial)
+{
+    __shared__ uint32_t s[8][32][4];
+    const int cv = threadIdx.x & 31, rl = threadIdx.x >> 5;
+    const int64_t vcol = (int64_t)blockIdx.x * 32 + cv;
+    const int64_t r0 = (int64_t)blockIdx.y * kColSlabRows;
+    const int64_t r1 = min(rows, r0 + (int64_t)kColSlabRows);
+    u16x2 m[4] = {};
+    if (vcol * 8 < cols) {
+        const uint16_t* base = x + (int64_t)blockIdx.z * batch_stride + vcol * 8;
+        for (int64_t r = r0 + rl; r < r1; r += 8)
+            fold_bf16x8(*reinterpret_cast<const u32x4*>(base + r * row_stride), m);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s[rl][cv][i] = __builtin_bit_cast(uint32_t, m[i]);
+    __syncthreads();
+    if (rl == 0 && vcol * 8 < cols) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            u16x2 a = m[i];
+            for (int k = 1; k < 8; ++k) a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, s[k][cv][i]));
+            uint32_t* out = partial + ((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * cols + vcol * 8 + 2 * i;
+            out[0] = (uint32_t)a[0] << 16;
+            out[1] = (uint32_t)a[1] << 16;
+        }
+    }
+}
+
+// Generic column groups (any dtype / alignment): one thread per column over a slab of rows.
+template <typename T> __global__ void __launch_bounds__(kThreads)
+absmax_cols_generic(const T* __restrict__ x, int64_t batch_stride, int64_t row_stride, int64_t rows, int64_t cols,
+                    uint32_t* __restrict__ partial)
+{
+    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (c >= cols) return;
+    const int64_t r0 = (int64_t)blockIdx.y * kColSlabRows;
+    const int64_t r1 = min(rows, r0 + (int64_t)kColSlabRows);
+    const T* base = x + (int64_t)blockIdx.z * batch_stride + c;
+    uint32_t m = 0;
+    for (int64_t r = r0; r < r1; ++r) m = max(m, mag_bits<T>(base[r * row_stride]));
+    partial[((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * cols + c] = m;
+}
+
+// Fold partial[b][P][C] over b == g (mod G) and over p, then delta = absmax / qmax.
+// C == 1: one workgroup per group.  C > 1: one thread per (g, c).
+__global__ void __launch_bounds__(kThreads)
+finalize_single(const uint32_t* __restrict__ partial, int64_t batch, int64_t P, int64_t G, float qmax,
+                float* __restrict__ delta)
+{
+    const int64_t g = blockIdx.x;
+    uint32_t m = 0;
+    for (int64_t b = g; b < batch; b += G)
+        for (int64_t p = threadIdx.x; p < P; p += kThreads) m = max(m, partial[b * P + p]);
+    m = block_max_u32(m);
+    if (threadIdx.x == 0) delta[g] = delta_from_absmax_bits(m, qmax);
+}
+__global__ void __launch_bounds__(kThreads)
+finalize_channels(const uint32_t* __restrict__ partial, int64_t batch, int64_t P, int64_t C, int64_t G, float qmax,
+                  float* __restrict__ delta)
+{
+    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t g = blockIdx.y;
+    if (c >= C) return;
+    uint32_t m = 0;
+    for (int64_t b = g; b < batch; b += G)
+        for (int64_t p = 0; p < P; ++p) m = max(m, partial[(b * P + p) * C + c]);
+    delta[g * C + c] = delta_from_absmax_bits(m, qmax);
+}
+
+struct Plan {
+    enum Kind { FLAT, ROWS, COLS_VEC, COLS_GENERIC } kind;
+    int64_t P;        // partials per matrix (per channel for the column kinds)
+    int64_t C;        // channels
+    int flat_blocks;
+};
+
+bool valid_tensor(const qmm_tensor* x, qmm_status* st)
+{
+    if (!x) { *st = QMM_ERR_NULL; return false; }
+    if (x->dtype != QMM_DT_BF16 && x->dtype != QMM_DT_F32) { *st = QMM_ERR_ENUM; return false; }
+    if (x->contract_axis != 0 && x->contract_axis != 1) { *st = QMM_ERR_ENUM; return false; }
+    if (x->batch < 0 || x->rows < 0 || x->cols < 0) { *st = QMM_ERR_SHAPE; return false; }
+    if (x->row_stride < x->cols) { *st = QMM_ERR_SHAPE; return false; }
+    if (x->batch > 1 && x->rows > 0 && x->batch_stride < (x->rows - 1) * x->row_stride + x->cols) {
+        *st = QMM_ERR_SHAPE; return false;
+    }
+    return true;
+}
+
+Plan make_plan(const qmm_tensor* x, const qmm_granularity* g)
+{
+    Plan p{};
+    const bool bf16 = x->dtype == QMM_DT_BF16;
+    const bool vec_ok = bf16 && aligned16(x->data) && (x->cols % 8 == 0) && (x->row_stride % 8 == 0) &&
+                        (x->batch_stride % 8 == 0);
+    if (!g->per_channel) {
+        p.C = 1;
+        const int64_t n = x->rows * x->cols;
+        if (vec_ok && x->row_stride == x->cols && n > 0) {
+            p.kind = Plan::FLAT;
+            const int64_t nvec = n / 8;
+            int64_t nb = (nvec + (int64_t)kThreads * 4 - 1) / ((int64_t)kThreads * 4);
+            const int64_t cap = x->batch > 1 ? (kMaxFlatBlocks + x->batch - 1) / x->batch : kMaxFlatBlocks;
+            nb = nb < 1 ? 1 : (nb > cap ? cap : nb);
+            p.flat_blocks = (int)nb;
+            p.P = nb;
+        } else {
+            p.kind = Plan::ROWS;
+            p.P = x->rows;
+        }
+    } else if (x->contract_axis == 1) {
+        p.kind = Plan::ROWS;
+        p.P = 1;
+        p.C = x->rows;
+    } else {
+        p.kind = vec_ok ? Plan::COLS_VEC : Plan::COLS_GENERIC;
+        p.P = (x->rows + kColSlabRows - 1) / kColSlabRows;
+        p.C = x->cols;
+    }
+    return p;
+}
+
+}  // namespace
+}  // namespace qmm
+
+using namespace qmm;
+
+extern "C" int64_t qmm_num_scales(const qmm_tensor* x, const qmm_granularity* g)
+{
+    if (!x || !g) return 0;
+    const int64_t c = g->per_channel ? (x->contract_axis == 1 ? x->rows : x->cols) : 1;
+    return g->batch_groups * c;
+}
+
+extern "C" size_t qmm_scale_workspace_size(const qmm_tensor* x, const qmm_granularity* g)
+{
+    qmm_status st;
+    if (!g || !valid_tensor(x, &st)) return 0;
+    const Plan p = make_plan(x, g);
+    const int64_t words = x->batch * p.P * p.C;
+    return (size_t)(words > 0 ? words : 1) * sizeof(uint32_t);
+}
+
+extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g, float* delta_out,
+                                void* workspace, size_t workspace_bytes, void* stream)
+{
+    qmm_status st;
+    if (!g || !delta_out) return QMM_ERR_NULL;
+    if (!valid_tensor(x, &st)) return st;
+    if (fmt != QMM_FMT_INT8 && fmt != QMM_FMT_E4M3 && fmt != QMM_FMT_E5M2) return QMM_ERR_ENUM;
+    if (g->batch_groups < 1 || g->reserved != 0 || (g->per_channel != 0 && g->per_channel != 1)) return QMM_ERR_ENUM;
+    const int64_t nscales = qmm_num_scales(x, g);
+    if (nscales == 0) return QMM_OK;
+    if (x->batch * x->rows * x->cols > 0 && !x->data) return QMM_ERR_NULL;
+    const size_t need = qmm_scale_workspace_size(x, g);
+    if (!workspace || workspace_bytes < need) return QMM_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return QMM_ERR_ALIGN;
+
+    hipStream_t s = as_stream(stream);
+    uint32_t* partial = static_cast<uint32_t*>(workspace);
+    const Plan p = make_plan(x, g);
+    const float qmax = fmt == QMM_FMT_INT8 ? 127.0f : (fmt == QMM_FMT_E4M3 ? 448.0f : 57344.0f);
+    const bool bf16 = x->dtype == QMM_DT_BF16;
+    const int64_t nelem = x->batch * x->rows * x->cols;
+    const int64_t C = p.C;
+    int64_t P = p.P;
+
+    if (nelem > 0) {
+        switch (p.kind) {
+        case Plan::FLAT:
+            absmax_flat_bf16<<<dim3(p.flat_blocks, (unsigned)x->batch), kThreads, 0, s>>>(
+                static_cast<const uint16_t*>(x->data), x->batch_stride, x->rows * x->cols / 8, partial);
+            break;
+        case Plan::ROWS: {
+            const int64_t total = x->batch * x->rows;
+            const unsigned nb = (unsigned)((total + kThreads / kWave - 1) / (kThreads / kWave));
+            if (bf16)
+                absmax_rows<uint16_t><<<nb, kThreads, 0, s>>>(static_cast<const uint16_t*>(x->data), x->batch_stride,
+                                                               x->row_stride, x->rows, x->cols, total, partial);
+            else
+                absmax_rows<float><<<nb, kThreads, 0, s>>>(static_cast<const float*>(x->data), x->batch_stride,
+                                                            x->row_stride, x->rows, x->cols, total, partial);
+            break;
+        }
+        case Plan::COLS_VEC:
+            absmax_cols_bf16<<<dim3((unsigned)((x->cols / 8 + 31) / 32), (unsigned)P, (unsigned)x->batch), kThreads, 0, s>>>(
+                static_cast<const uint16_t*>(x->data), x->batch_stride, x->row_stride, x->rows, x->cols, partial);
+            break;
+        case Plan::COLS_GENERIC: {
+            const dim3 grid((unsigned)((x->cols + kThreads - 1) / kThreads), (unsigned)P, (unsigned)x->batch);
+            if (bf16)
+                absmax_cols_generic<uint16_t><<<grid, kThreads, 0, s>>>(static_cast<const uint16_t*>(x->data),
+                                                                        x->batch_stride, x->row_stride, x->rows, x->cols, partial);
+            else
+                absmax_cols_generic<float><<<grid, kThreads, 0, s>>>(static_cast<const float*>(x->data), x->batch_stride,
+                                                                     x->row_stride, x->rows, x->cols, partial);
+            break;
+        }
+        }
+        if (hipGetLastError() != hipSuccess) return QMM_ERR_LAUNCH;
+    }
+    // An empty tensor has no partials: fold over zero matrices so every group gets delta = 1.
+    const int64_t fold_batch = nelem > 0 ? x->batch : 0;
+    if (nelem == 0) P = 0;
+    const int64_t G = g->batch_groups;
+    if (C == 1)
+        finalize_single<<<(unsigned)G, kThreads, 0, s>>>(partial, fold_batch, P, G, qmax, delta_out);
+    else
+        finalize_channels<<<dim3((unsigned)((C + kThreads - 1) / kThreads), (unsigned)G), kThreads, 0, s>>>(
+            partial, fold_batch, P, C, G, qmax, delta_out);
+    return launch_status();
+}

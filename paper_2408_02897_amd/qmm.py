@@ -1,0 +1,196 @@
+"""Thin ctypes binding of libqmm.so (include/qmm.h).  Argument marshalling only: every step of the
+path runs in the HIP kernels.  torch is used for device memory and the current stream.  There is no
+CPU fallback: a missing or unloadable library raises."""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqmm.so")
+
+INT8, E4M3, E5M2, BF16 = 0, 1, 2, 3
+DT_BF16, DT_F32 = 0, 1
+RTNE, STOCHASTIC = 0, 1
+FORMATS = {"int8": INT8, "e4m3": E4M3, "e5m2": E5M2, "bf16": BF16}
+EXPORTS = ["qmm_num_scales", "qmm_scale_workspace_size", "qmm_scale", "qmm_quantize", "qmm_gemm_workspace_size",
+           "qmm_gemm", "qmm_metric_workspace_size", "qmm_metric", "qmm_status_string", "qmm_version"]
+
+
+class QmmError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({status_string(status)})")
+
+
+class Tensor(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("dtype", ctypes.c_int32), ("contract_axis", ctypes.c_int32),
+                ("batch", ctypes.c_int64), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("batch_stride", ctypes.c_int64), ("row_stride", ctypes.c_int64)]
+
+
+class Granularity(ctypes.Structure):
+    _fields_ = [("per_channel", ctypes.c_int32), ("reserved", ctypes.c_int32), ("batch_groups", ctypes.c_int64)]
+
+
+class Operand(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("format", ctypes.c_int32), ("is_codes", ctypes.c_int32),
+                ("delta", ctypes.c_void_p), ("gran", Granularity)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libqmm.so (built in-tree by paper_2408_02897_amd.build).  Raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2408_02897_amd.build` first "
+                               "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, u64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t
+        TP, GP, OP = ctypes.POINTER(Tensor), ctypes.POINTER(Granularity), ctypes.POINTER(Operand)
+        L.qmm_num_scales.restype = i64; L.qmm_num_scales.argtypes = [TP, GP]
+        L.qmm_scale_workspace_size.restype = sz; L.qmm_scale_workspace_size.argtypes = [TP, GP]
+        L.qmm_scale.restype = i32; L.qmm_scale.argtypes = [TP, i32, GP, vp, vp, sz, vp]
+        L.qmm_quantize.restype = i32; L.qmm_quantize.argtypes = [TP, i32, GP, vp, i32, u64, u64, vp, vp]
+        L.qmm_gemm_workspace_size.restype = sz; L.qmm_gemm_workspace_size.argtypes = [OP, OP, i64, i64, i64, i64]
+        L.qmm_gemm.restype = i32; L.qmm_gemm.argtypes = [OP, OP, i64, i64, i64, i64, vp, i32, vp, vp, sz, vp]
+        L.qmm_metric_workspace_size.restype = sz; L.qmm_metric_workspace_size.argtypes = [i64]
+        L.qmm_metric.restype = i32; L.qmm_metric.argtypes = [vp, i32, vp, vp, i64, vp, vp, sz, vp]
+        L.qmm_status_string.restype = ctypes.c_char_p; L.qmm_status_string.argtypes = [i32]
+        L.qmm_version.restype = i32; L.qmm_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().qmm_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != 0:
+        raise QmmError(status, where)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.bfloat16:
+        return DT_BF16
+    if t.dtype == torch.float32:
+        return DT_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def tensor_desc(x, contract_axis):
+    """Descriptor of a 2-D [rows, cols] or 3-D [batch, rows, cols] device tensor with contiguous columns."""
+    if x.dim() == 2:
+        x = x.unsqueeze(0)
+    assert x.dim() == 3 and x.is_cuda
+    assert x.stride(2) == 1 or x.shape[2] <= 1, "columns must be contiguous"
+    b, r, c = x.shape
+    return Tensor(x.data_ptr(), _dtype_code(x), contract_axis, b, r, c, x.stride(0), x.stride(1))
+
+
+def granularity(per_channel=False, batch_groups=1):
+    return Granularity(int(per_channel), 0, int(batch_groups))
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+def scale(x, contract_axis, fmt, per_channel=False, batch_groups=1, out=None, workspace=None):
+    """qmm_scale: step sizes (float32 device tensor of qmm_num_scales elements)."""
+    L = lib()
+    t, g = tensor_desc(x, contract_axis), granularity(per_channel, batch_groups)
+    n = L.qmm_num_scales(ctypes.byref(t), ctypes.byref(g))
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=x.device)
+    need = L.qmm_scale_workspace_size(ctypes.byref(t), ctypes.byref(g))
+    if workspace is None:
+        workspace = _workspace(need, x.device)
+    _check(L.qmm_scale(ctypes.byref(t), fmt, ctypes.byref(g), out.data_ptr(), workspace.data_ptr(),
+                       workspace.numel(), _stream()), "qmm_scale")
+    return out
+
+
+def quantize(x, contract_axis, fmt, delta, per_channel=False, batch_groups=1, mode=RTNE, seed=0, offset=0, out=None):
+    """qmm_quantize: uint8 codes [batch, non-contracting, contracting]."""
+    L = lib()
+    t, g = tensor_desc(x, contract_axis), granularity(per_channel, batch_groups)
+    nc, kc = (t.rows, t.cols) if contract_axis == 1 else (t.cols, t.rows)
+    if out is None:
+        out = torch.empty((t.batch, nc, kc), dtype=torch.uint8, device=x.device)
+    assert delta.dtype == torch.float32 and delta.numel() == L.qmm_num_scales(ctypes.byref(t), ctypes.byref(g))
+    _check(L.qmm_quantize(ctypes.byref(t), fmt, ctypes.byref(g), delta.data_ptr(), mode, seed, offset,
+                          out.data_ptr(), _stream()), "qmm_quantize")
+    return out
+
+
+def operand(data, fmt, delta=None, per_channel=False, batch_groups=1, is_codes=True):
+    assert data.is_contiguous()
+    return Operand(data.data_ptr(), fmt, int(is_codes), delta.data_ptr() if delta is not None else None,
+                   granularity(per_channel, batch_groups))
+
+
+def gemm(a, b, out_dtype=torch.float32, want_acc=False, out=None, acc_out=None, want_y=True):
+    """qmm_gemm on two (data, Operand) pairs built by `operand`: a = (tensor [batch,M,K], Operand) etc.
+    Returns y (and the raw accumulators when want_acc)."""
+    L = lib()
+    (ta, oa), (tb, ob) = a, b
+    if ta.dim() == 2:
+        ta = ta.unsqueeze(0); tb = tb.unsqueeze(0)
+    bt, m, k = ta.shape
+    n = tb.shape[1]
+    assert tb.shape[0] == bt and tb.shape[2] == k
+    dev = ta.device
+    y = out
+    if y is None and want_y:
+        y = torch.empty((bt, m, n), dtype=out_dtype, device=dev)
+    acc = acc_out
+    if acc is None and want_acc:
+        acc = torch.empty((bt, m, n), dtype=torch.int32 if oa.format == INT8 else torch.float32, device=dev)
+    need = L.qmm_gemm_workspace_size(ctypes.byref(oa), ctypes.byref(ob), bt, m, n, k)
+    ws = _workspace(need, dev)
+    ydt = DT_BF16 if (y is not None and y.dtype == torch.bfloat16) else DT_F32
+    _check(L.qmm_gemm(ctypes.byref(oa), ctypes.byref(ob), bt, m, n, k, y.data_ptr() if y is not None else None, ydt,
+                      acc.data_ptr() if acc is not None else None, ws.data_ptr(), ws.numel(), _stream()), "qmm_gemm")
+    return (y, acc) if want_acc else y
+
+
+def quantized_operand(x, contract_axis, fmt, per_channel=False, batch_groups=1, mode=RTNE, seed=0):
+    """scale + quantize; returns ((codes, Operand), delta)."""
+    d = scale(x, contract_axis, fmt, per_channel, batch_groups)
+    c = quantize(x, contract_axis, fmt, d, per_channel, batch_groups, mode, seed)
+    return (c, operand(c, fmt, d, per_channel, batch_groups)), d
+
+
+def reference_gemm(x, w, out=None):
+    """High-precision product of bfloat16 operands x [batch,M,K], w [batch,N,K] -> float32."""
+    assert x.dtype == torch.bfloat16 and w.dtype == torch.bfloat16
+    x = x.contiguous(); w = w.contiguous()
+    return gemm((x, operand(x, BF16, is_codes=False)), (w, operand(w, BF16, is_codes=False)), torch.float32, out=out)
+
+
+def metric(y, y_ref, denom=None, out=None, workspace=None):
+    """qmm_metric: 16 float64 on the device (layout in include/qmm.h)."""
+    L = lib()
+    assert y.is_contiguous() and y_ref.is_contiguous() and y_ref.dtype == torch.float32
+    n = y.numel()
+    assert y_ref.numel() == n and (denom is None or (denom.numel() == n and denom.dtype == torch.float32))
+    if out is None:
+        out = torch.empty(16, dtype=torch.float64, device=y.device)
+    if workspace is None:
+        workspace = _workspace(L.qmm_metric_workspace_size(n), y.device)
+    _check(L.qmm_metric(y.data_ptr(), _dtype_code(y), y_ref.data_ptr(), denom.data_ptr() if denom is not None else None,
+                        n, out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()), "qmm_metric")
+    return out
+
+
+METRIC_FIELDS = ("S_ee", "S_rr", "S_ae", "S_ar", "M_e", "M_r", "RE_sum", "RE_max", "RE_cnt",
+                 "BE_sum", "BE_max", "BE_cnt", "n", "nan_cnt", "rsv0", "rsv1")

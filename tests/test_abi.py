@@ -1,0 +1,69 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol include/qmm.h declares, and
+rejects bad arguments before touching the GPU (so these calls are safe without one)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2408_02897_amd import qmm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(qmm.LIB_PATH):
+        from paper_2408_02897_amd import build
+        build.build()
+    return qmm.lib()
+
+
+def test_exports_match_header(L):
+    hdr = open(os.path.join(ROOT, "include", "qmm.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(qmm_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(qmm.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert L.qmm_version() == 100
+    assert qmm.status_string(0) == "ok" and "NULL" in qmm.status_string(1)
+
+
+def test_num_scales_and_workspace_sizes(L):
+    t = qmm.Tensor(None, qmm.DT_BF16, 1, 4, 10, 32, 320, 32)
+    g = qmm.granularity(False, 1)
+    assert L.qmm_num_scales(ctypes.byref(t), ctypes.byref(g)) == 1
+    g = qmm.granularity(True, 2)
+    assert L.qmm_num_scales(ctypes.byref(t), ctypes.byref(g)) == 20
+    t.contract_axis = 0
+    assert L.qmm_num_scales(ctypes.byref(t), ctypes.byref(g)) == 64
+    assert L.qmm_scale_workspace_size(ctypes.byref(t), ctypes.byref(g)) >= 4 * 32 * 4
+    assert L.qmm_metric_workspace_size(0) >= 128 and L.qmm_metric_workspace_size(1 << 30) <= 2048 * 128
+
+
+def test_argument_errors_are_reported_before_any_launch(L):
+    g = qmm.granularity(False, 1)
+    t = qmm.Tensor(None, qmm.DT_BF16, 1, 1, 4, 16, 64, 16)
+    fake = ctypes.c_void_p(0x1000)
+    # NULL output
+    assert L.qmm_scale(ctypes.byref(t), qmm.E4M3, ctypes.byref(g), None, fake, 1024, None) == 1
+    # bad format / bad axis / bad shape / missing workspace
+    assert L.qmm_scale(ctypes.byref(t), 7, ctypes.byref(g), fake, fake, 1024, None) == 3
+    t2 = qmm.Tensor(None, qmm.DT_BF16, 2, 1, 4, 16, 64, 16)
+    assert L.qmm_scale(ctypes.byref(t2), qmm.E4M3, ctypes.byref(g), fake, fake, 1024, None) == 3
+    t3 = qmm.Tensor(None, qmm.DT_BF16, 1, 1, 4, 16, 64, 8)
+    assert L.qmm_scale(ctypes.byref(t3), qmm.E4M3, ctypes.byref(g), fake, fake, 1024, None) == 2
+    t4 = qmm.Tensor(fake, qmm.DT_BF16, 1, 1, 4, 16, 64, 16)
+    assert L.qmm_scale(ctypes.byref(t4), qmm.E4M3, ctypes.byref(g), fake, None, 0, None) == 6
+    assert L.qmm_quantize(ctypes.byref(t4), qmm.E4M3, ctypes.byref(g), fake, 5, 0, 0, fake, None) == 3
+    assert L.qmm_quantize(ctypes.byref(t4), qmm.E4M3, ctypes.byref(g), None, 0, 0, 0, fake, None) == 1
+    oa = qmm.Operand(fake, qmm.E4M3, 1, fake, g); ob = qmm.Operand(fake, qmm.INT8, 1, fake, g)
+    assert L.qmm_gemm(ctypes.byref(oa), ctypes.byref(ob), 1, 16, 16, 16, fake, 1, None, None, 0, None) == 5
+    ob = qmm.Operand(fake, qmm.E5M2, 1, fake, g)
+    assert L.qmm_gemm(ctypes.byref(oa), ctypes.byref(ob), 1, 16, 16, 24, fake, 1, None, None, 0, None) == 4
+    assert L.qmm_gemm(ctypes.byref(oa), ctypes.byref(ob), 1, 16, 16, 32, None, 1, None, None, 0, None) == 1
+    assert L.qmm_gemm(ctypes.byref(oa), ctypes.byref(ob), 1, -1, 16, 32, fake, 1, None, None, 0, None) == 2
+    assert L.qmm_metric(fake, 1, fake, None, 8, None, fake, 1 << 20, None) == 1
+    assert L.qmm_metric(fake, 1, fake, None, 8, fake, None, 0, None) == 6
+    assert L.qmm_metric(fake, 9, fake, None, 8, fake, fake, 1 << 20, None) == 3

@@ -1,0 +1,283 @@
+"""GPU parity: every call of the C-ABI library against the CPU oracle, element by element, on seeded
+inputs.  Bars: bit-exact for step sizes, codes, INT8 accumulators and INT8-path outputs; FP8
+accumulators within 1e-5 * sum_k|a||b| component-wise (summation order differs; bound from the
+arithmetic: K * 2^-24 * S is the textbook worst case, observed error is far below); metric sums
+within 1e-10 relative on identical inputs (binary64 sums in a different order), counts and maxima exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2408_02897_amd import qmm, workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+FMTS = [qmm.INT8, qmm.E4M3, qmm.E5M2]
+FP8_TOL = 1e-5
+
+
+def np32(t):
+    return t.detach().float().cpu().numpy()
+
+
+def all_bf16_patterns():
+    bits = torch.arange(65536, dtype=torch.int32).to(torch.int16)
+    return bits.view(torch.bfloat16)
+
+
+# ------------------------------------------------------------------------ scale
+@pytest.mark.parametrize("shape,contract_axis,per_channel,groups", [
+    ((1, 256, 768), 1, False, 1), ((1, 768, 768), 1, True, 1), ((1, 300, 520), 0, True, 1),
+    ((1, 777, 1024), 1, False, 1), ((6, 64, 96), 1, False, 3), ((6, 64, 96), 1, True, 2),
+    ((6, 70, 96), 0, True, 3), ((4, 33, 50), 1, False, 1), ((4, 33, 50), 0, True, 2), ((4, 33, 50), 1, True, 4),
+    ((1, 4096, 2048), 1, False, 1), ((1, 1, 8), 1, False, 1), ((2, 1000, 72), 0, False, 2),
+])
+@pytest.mark.parametrize("fmt", FMTS)
+def test_scale_bit_exact(shape, contract_axis, per_channel, groups, fmt):
+    x = W.student_t(shape, 4, seed=sum(shape) + contract_axis)
+    want = O.scale(np32(x), contract_axis, fmt, per_channel, groups)
+    got = qmm.scale(x.to(DEV), contract_axis, fmt, per_channel, groups)
+    assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+def test_scale_f32_input_strided_and_special_values():
+    g = torch.Generator(); g.manual_seed(3)
+    base = torch.randn((3, 40, 64), generator=g)
+    view = base[:, :37, :56]                                      # row_stride 64 > cols 56
+    for ca, pc in ((1, False), (1, True), (0, True)):
+        want = O.scale(view.contiguous().numpy(), ca, O.E4M3, pc, 1)
+        got = qmm.scale(view.to(DEV).contiguous(), ca, qmm.E4M3, pc, 1)
+        assert np.array_equal(got.cpu().numpy(), want)
+        xb = base.to(torch.bfloat16).to(DEV)[:, :37, :56]          # strided bf16 view on the device
+        want = O.scale(np32(xb), ca, O.E5M2, pc, 1)
+        assert np.array_equal(qmm.scale(xb, ca, qmm.E5M2, pc, 1).cpu().numpy(), want)
+    z = torch.zeros((2, 16, 32), dtype=torch.bfloat16)
+    z[1, 3, 5] = float("inf")
+    for groups in (1, 2):
+        want = O.scale(np32(z), 1, O.INT8, False, groups)
+        got = qmm.scale(z.to(DEV), 1, qmm.INT8, False, groups).cpu().numpy()
+        assert np.array_equal(got, want) and (groups == 1 or got[0] == 1.0)
+    z[0, 0, 0] = float("nan")
+    got = qmm.scale(z.to(DEV), 1, qmm.INT8, False, 1).cpu().numpy()
+    assert np.isnan(got[0])
+    tiny = torch.full((1, 8, 16), 2.0 ** -133, dtype=torch.bfloat16)
+    assert qmm.scale(tiny.to(DEV), 1, qmm.E4M3).item() == 2.0 ** -126
+    empty = torch.zeros((1, 0, 16), dtype=torch.bfloat16, device=DEV)
+    assert qmm.scale(empty, 1, qmm.E4M3).item() == 1.0
+
+
+# --------------------------------------------------------------------- quantize
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("mode", [qmm.RTNE, qmm.STOCHASTIC])
+def test_quantize_every_bf16_pattern_many_step_sizes(fmt, mode):
+    """All 65 536 bfloat16 bit patterns (NaNs, infs, subnormals, both zeros) under 16 step sizes, one per row."""
+    pats = all_bf16_patterns()
+    deltas = torch.tensor([1.0, 0.5, 3.0, 1e-3, 7.77e-5, 123.456, 2.0 ** -126, 1.0 / 448, 1.0 / 127, 57344.0,
+                           1e10, 1e-20, 0.0123, 2.0 ** -20, 17.0, 0.3333], dtype=torch.float32)
+    x = pats.unsqueeze(0).repeat(16, 1).contiguous()               # [16, 65536]
+    want = O.quantize(np32(x), 1, fmt, deltas.numpy(), per_channel=True, mode=mode, seed=42, offset=7)
+    got = qmm.quantize(x.to(DEV), 1, fmt, deltas.to(DEV), per_channel=True, mode=mode, seed=42, offset=7)
+    g, w = got.cpu().numpy(), want
+    bad = np.nonzero(g != w)
+    assert bad[0].size == 0, f"first mismatch at {[b[0] for b in bad]}: got {g[bad][0]:#x} want {w[bad][0]:#x}"
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("shape,contract_axis,per_channel,groups", [
+    ((1, 256, 768), 1, False, 1), ((1, 768, 768), 1, True, 1), ((1, 300, 520), 0, True, 1), ((1, 300, 520), 0, False, 1),
+    ((6, 64, 96), 1, True, 2), ((6, 70, 96), 0, True, 3), ((4, 33, 50), 1, False, 1), ((4, 33, 50), 0, True, 2),
+    ((2, 130, 136), 0, False, 2), ((1, 1024, 256), 0, True, 1),
+])
+def test_quantize_paths_bit_exact(fmt, shape, contract_axis, per_channel, groups):
+    x = W.student_t(shape, 4, seed=17 + shape[1])
+    xd = x.to(DEV)
+    d = qmm.scale(xd, contract_axis, fmt, per_channel, groups)
+    want_d = O.scale(np32(x), contract_axis, fmt, per_channel, groups)
+    assert np.array_equal(d.cpu().numpy(), want_d)
+    for mode in (qmm.RTNE, qmm.STOCHASTIC):
+        want = O.quantize(np32(x), contract_axis, fmt, want_d, per_channel, groups, mode, seed=5, offset=3)
+        got = qmm.quantize(xd, contract_axis, fmt, d, per_channel, groups, mode, seed=5, offset=3)
+        assert got.shape == want.shape
+        assert np.array_equal(got.cpu().numpy(), want), f"mode {mode}"
+
+
+def test_quantize_f32_input_and_gradient_like_values():
+    x = W.lognormal_signed((2, 96, 80), -8.0, 2.0, seed=8).float()
+    for fmt in FMTS:
+        d = qmm.scale(x.to(DEV), 1, fmt, True, 1)
+        want_d = O.scale(x.numpy(), 1, fmt, True, 1)
+        assert np.array_equal(d.cpu().numpy(), want_d)
+        got = qmm.quantize(x.to(DEV), 1, fmt, d, True, 1)
+        assert np.array_equal(got.cpu().numpy(), O.quantize(x.numpy(), 1, fmt, want_d, True, 1))
+
+
+# ------------------------------------------------------------------------- gemm
+def _random_codes(fmt, shape, seed):
+    g = torch.Generator(); g.manual_seed(seed)
+    c = torch.randint(0, 256, shape, generator=g, dtype=torch.int32).to(torch.uint8).numpy()
+    v = O.decode(fmt, c)
+    c[~np.isfinite(v)] = 0x31
+    if fmt == O.INT8:
+        c[c == 0x80] = 0x81
+    return c
+
+
+GEMM_SHAPES = [(1, 16, 16, 16), (1, 128, 128, 128), (1, 256, 768, 768), (1, 200, 136, 400), (1, 300, 272, 144),
+               (3, 130, 80, 64), (1, 520, 528, 1040), (2, 257, 512, 272), (1, 64, 1000, 48)]
+
+
+@pytest.mark.parametrize("shape", GEMM_SHAPES)
+def test_gemm_int8_bit_exact(shape):
+    bt, M, N, K = shape
+    a = _random_codes(O.INT8, (bt, M, K), 1); b = _random_codes(O.INT8, (bt, N, K), 2)
+    rng = np.random.default_rng(5)
+    da = rng.uniform(1e-3, 1e-2, M).astype(np.float32); db = rng.uniform(1e-3, 1e-2, N).astype(np.float32)
+    want_acc = O.gemm_int8(a, b)
+    ta, tb = torch.from_numpy(a).to(DEV), torch.from_numpy(b).to(DEV)
+    tda, tdb = torch.from_numpy(da).to(DEV), torch.from_numpy(db).to(DEV)
+    for pc in (False, True):
+        oa = qmm.operand(ta, qmm.INT8, tda, pc); ob = qmm.operand(tb, qmm.INT8, tdb, pc)
+        y, acc = qmm.gemm((ta, oa), (tb, ob), torch.float32, want_acc=True)
+        assert np.array_equal(acc.cpu().numpy().astype(np.int64), want_acc)
+        want_y = O.dequant(want_acc.astype(np.float64), da if pc else da[:1], db if pc else db[:1], pc, 1, pc, 1)
+        assert np.array_equal(y.cpu().numpy().view(np.uint32), want_y.view(np.uint32))
+        yb = qmm.gemm((ta, oa), (tb, ob), torch.bfloat16)
+        want_yb = O.dequant(want_acc.astype(np.float64), da if pc else da[:1], db if pc else db[:1], pc, 1, pc, 1, True)
+        assert np.array_equal(np32(yb).view(np.uint32), want_yb.view(np.uint32))
+
+
+def test_gemm_int8_worst_case_and_one_hot():
+    K = 16384
+    a = np.full((1, 32, K), 127, np.int8); b = np.full((1, 16, K), -127, np.int8)
+    ta, tb = torch.from_numpy(a.view(np.uint8)).to(DEV), torch.from_numpy(b.view(np.uint8)).to(DEV)
+    one = torch.ones(1, device=DEV)
+    _, acc = qmm.gemm((ta, qmm.operand(ta, qmm.INT8, one)), (tb, qmm.operand(tb, qmm.INT8, one)), want_acc=True)
+    assert torch.all(acc == -16129 * K)
+    # one-hot operands: exactly one output element is set, at (i, j), for several (i, j, k)
+    M, N, K = 160, 208, 256
+    for (i, j, k, va, vb) in [(0, 0, 0, 3, 5), (17, 33, 129, -7, 9), (159, 207, 255, 127, -127), (100, 64, 63, 2, 2), (31, 15, 64, 1, -1)]:
+        a = np.zeros((1, M, K), np.int8); b = np.zeros((1, N, K), np.int8)
+        a[0, i, k] = va; b[0, j, k] = vb
+        ta, tb = torch.from_numpy(a.view(np.uint8)).to(DEV), torch.from_numpy(b.view(np.uint8)).to(DEV)
+        _, acc = qmm.gemm((ta, qmm.operand(ta, qmm.INT8, one)), (tb, qmm.operand(tb, qmm.INT8, one)), want_acc=True)
+        acc = acc.cpu().numpy()
+        assert acc[0, i, j] == va * vb and np.count_nonzero(acc) == 1, (i, j, k)
+
+
+@pytest.mark.parametrize("shape", GEMM_SHAPES)
+@pytest.mark.parametrize("fa,fb", [(qmm.E4M3, qmm.E4M3), (qmm.E5M2, qmm.E4M3), (qmm.E4M3, qmm.E5M2), (qmm.E5M2, qmm.E5M2)])
+def test_gemm_fp8_within_tolerance(shape, fa, fb):
+    bt, M, N, K = shape
+    a = _random_codes(fa, (bt, M, K), 3); b = _random_codes(fb, (bt, N, K), 4)
+    # keep magnitudes moderate so products stay far from the binary32 range limits (E5M2 max^2 ~ 3e9 is fine)
+    want_acc, sabs = O.gemm_codes(a, fa, b, fb)
+    ta, tb = torch.from_numpy(a).to(DEV), torch.from_numpy(b).to(DEV)
+    rng = np.random.default_rng(6)
+    da = rng.uniform(1e-3, 1e-2, M).astype(np.float32); db = rng.uniform(1e-3, 1e-2, N).astype(np.float32)
+    tda, tdb = torch.from_numpy(da).to(DEV), torch.from_numpy(db).to(DEV)
+    oa = qmm.operand(ta, fa, tda, True); ob = qmm.operand(tb, fb, tdb, True)
+    y, acc = qmm.gemm((ta, oa), (tb, ob), torch.float32, want_acc=True)
+    acc = acc.cpu().numpy().astype(np.float64)
+    err = np.abs(acc - want_acc)
+    assert np.all(err <= FP8_TOL * sabs + 1e-30), f"max ratio {np.max(err / (sabs + 1e-300)):.3e}"
+    # descale applied to the device's own accumulators must be exact binary32 arithmetic
+    want_y = O.dequant(acc, da, db, True, 1, True, 1)
+    assert np.array_equal(y.cpu().numpy().view(np.uint32), want_y.view(np.uint32))
+
+
+def test_gemm_fp8_exact_cases():
+    """Powers of two and one-hot inputs give exact binary32 sums in any order."""
+    M, N, K = 144, 80, 384
+    rng = np.random.default_rng(9)
+    # codes of +-2^e only: E4M3 exponent field 1..14 with zero mantissa
+    ea = rng.integers(5, 9, (1, M, K)); eb = rng.integers(5, 9, (1, N, K))
+    a = ((ea << 3) | (rng.integers(0, 2, ea.shape) << 7)).astype(np.uint8)
+    b = ((eb << 3) | (rng.integers(0, 2, eb.shape) << 7)).astype(np.uint8)
+    want = O.gemm_codes(a, O.E4M3, b, O.E4M3, want_sabs=False)
+    ta, tb = torch.from_numpy(a).to(DEV), torch.from_numpy(b).to(DEV)
+    one = torch.ones(1, device=DEV)
+    _, acc = qmm.gemm((ta, qmm.operand(ta, qmm.E4M3, one)), (tb, qmm.operand(tb, qmm.E4M3, one)), want_acc=True)
+    assert np.array_equal(acc.cpu().numpy().astype(np.float64), want)
+    for (i, j, k) in [(0, 0, 0), (143, 79, 383), (77, 31, 200), (16, 16, 127), (15, 63, 128)]:
+        a = np.zeros((1, M, K), np.uint8); b = np.zeros((1, N, K), np.uint8)
+        a[0, i, k] = 0x45; b[0, j, k] = 0xC2                      # E5M2 5.0 and -3.0
+        ta, tb = torch.from_numpy(a).to(DEV), torch.from_numpy(b).to(DEV)
+        _, acc = qmm.gemm((ta, qmm.operand(ta, qmm.E5M2, one)), (tb, qmm.operand(tb, qmm.E5M2, one)), want_acc=True)
+        acc = acc.cpu().numpy()
+        assert acc[0, i, j] == -15.0 and np.count_nonzero(acc) == 1, (i, j, k)
+
+
+def test_gemm_per_head_scales_and_batch_groups():
+    bt, M, N, K, H = 8, 48, 64, 64, 4
+    a = _random_codes(O.E4M3, (bt, M, K), 11); b = _random_codes(O.E4M3, (bt, N, K), 12)
+    rng = np.random.default_rng(1)
+    da = rng.uniform(0.5, 2.0, H).astype(np.float32); db = rng.uniform(0.5, 2.0, bt).astype(np.float32)
+    ta, tb = torch.from_numpy(a).to(DEV), torch.from_numpy(b).to(DEV)
+    oa = qmm.operand(ta, qmm.E4M3, torch.from_numpy(da).to(DEV), False, H)
+    ob = qmm.operand(tb, qmm.E4M3, torch.from_numpy(db).to(DEV), False, bt)
+    y, acc = qmm.gemm((ta, oa), (tb, ob), want_acc=True)
+    want_y = O.dequant(acc.cpu().numpy().astype(np.float64), da, db, False, H, False, bt)
+    assert np.array_equal(y.cpu().numpy(), want_y)
+    want_acc, sabs = O.gemm_codes(a, O.E4M3, b, O.E4M3)
+    assert np.all(np.abs(acc.cpu().numpy() - want_acc) <= FP8_TOL * sabs)
+
+
+def test_reference_gemm():
+    for (bt, M, N, K) in [(1, 256, 768, 768), (2, 100, 72, 200), (1, 130, 258, 520)]:
+        x = W.normal((bt, M, K), 1.0, 5); w = W.normal((bt, N, K), 0.02, 6)
+        r = qmm.reference_gemm(x.to(DEV), w.to(DEV)).cpu().numpy()
+        want = O.ref_gemm(np32(x), np32(w))
+        sabs = np.einsum("bik,bjk->bij", np.abs(np32(x)).astype(np.float64), np.abs(np32(w)).astype(np.float64))
+        assert np.all(np.abs(r.astype(np.float64) - want) <= 1e-5 * sabs)
+
+
+# ----------------------------------------------------------------------- metric
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 1000, 4099, 1 << 20, (1 << 22) + 5])
+@pytest.mark.parametrize("y_bf16", [False, True])
+@pytest.mark.parametrize("with_d", [False, True])
+def test_metric_parity(n, y_bf16, with_d):
+    g = torch.Generator(); g.manual_seed(n + 1)
+    r = torch.randn(n, generator=g)
+    y = r + 1e-3 * torch.randn(n, generator=g)
+    d = torch.randn(n, generator=g).abs()
+    if n >= 1000:
+        r[::97] = 0.0; d[::101] = 0.0
+        y[5] = float("nan"); r[6] = float("nan"); y[7] = float("inf"); r[7] = float("inf")
+    if y_bf16:
+        y = y.to(torch.bfloat16)
+    want = O.metric(np32(y), r.numpy(), d.numpy() if with_d else None)
+    got = qmm.metric(y.to(DEV), r.to(DEV), d.to(DEV) if with_d else None).cpu().numpy()
+    for i in (4, 5, 7, 8, 10, 11, 12, 13, 14, 15):                # maxima and counts: exact
+        assert got[i] == want[i], (i, got[i], want[i])
+    for i in (0, 1, 2, 3, 6, 9):
+        assert abs(got[i] - want[i]) <= 1e-10 * abs(want[i]), (i, got[i], want[i])
+
+
+# ----------------------------------------------------------- the whole path
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("per_channel", [False, True])
+def test_single_linear_end_to_end(fmt, per_channel):
+    """X 256x768 ~ N(0,1), W 768x768 ~ N(0, 0.02^2), seed 0: every intermediate against the oracle."""
+    x, w = W.single_linear(0)
+    y_o, acc_o, sabs, dx_o, dw_o, cx_o, cw_o = O.quantized_matmul(np32(x), np32(w), fmt, fmt, per_channel)
+    r_o = O.ref_gemm(np32(x), np32(w))
+    xd, wd = x.to(DEV), w.to(DEV)
+    (cx, ox), dx = qmm.quantized_operand(xd, 1, fmt, per_channel)
+    (cw, ow), dw = qmm.quantized_operand(wd, 1, fmt, per_channel)
+    assert np.array_equal(dx.cpu().numpy(), dx_o) and np.array_equal(dw.cpu().numpy(), dw_o)
+    assert np.array_equal(cx.cpu().numpy(), cx_o) and np.array_equal(cw.cpu().numpy(), cw_o)
+    y, acc = qmm.gemm((cx, ox), (cw, ow), torch.float32, want_acc=True)
+    r = qmm.reference_gemm(xd.unsqueeze(0), wd.unsqueeze(0))
+    if fmt == qmm.INT8:
+        assert np.array_equal(acc.cpu().numpy().astype(np.float64), acc_o)
+        assert np.array_equal(y.cpu().numpy(), y_o)
+    else:
+        assert np.all(np.abs(acc.cpu().numpy() - acc_o) <= FP8_TOL * sabs)
+    m = qmm.metric(y, r).cpu().numpy()
+    m_o = O.metric(y_o, r_o)
+    nsr, nsr_o = m[0] / m[1], m_o[0] / m_o[1]
+    assert abs(nsr - nsr_o) <= 1e-4 * nsr_o
+    # the metric pass itself on identical inputs
+    m_same = O.metric(y.cpu().numpy(), r.cpu().numpy())
+    assert np.allclose(m, m_same, rtol=1e-10, atol=0)
