@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-matmul hot path on one MI355X.
+
+One "step" = one pass of the whole path over the forward GEMMs of one BERT-large encoder layer
+(16384 tokens, hidden 1024, FFN 4096: QKV, attention output, FFN1, FFN2): for every op
+    qmm_scale(X), qmm_scale(W), qmm_quantize(X), qmm_quantize(W), qmm_gemm (+descale, bf16 out), qmm_metric(Y, Y_ref)
+with E4M3 operands, per-tensor step sizes, synthetic seeded inputs already resident in HBM.  The
+high-precision reference product Y_ref is an input of the metric pass and is computed once, outside
+the timed region (it is the un-quantized baseline the method compares against, not part of the
+quantized path).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_large_fwd|bert_base_fwd]
+                    [--format e4m3|e5m2|int8] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"e4m3": 5000.0, "e5m2": 5000.0, "int8": 5000.0}   # dense MFMA TFLOP/s (TOP/s), MI355X
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="bert_large_fwd", choices=["bert_large_fwd", "bert_base_fwd"])
+    ap.add_argument("--format", default="e4m3", choices=["e4m3", "e5m2", "int8"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2408_02897_amd import qmm, workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    fmt = qmm.FORMATS[args.format]
+    cfg_no, dims = (4, W.BERT_LARGE) if args.workload == "bert_large_fwd" else (2, W.BERT_BASE)
+    ops = W.bert_forward_ops(**dims)
+
+    # ---- inputs, resident in HBM; reference products (untimed)
+    state = []
+    for op in ops:
+        x, w = W.forward_operands(op, cfg_no, layer=0)
+        xd, wd = x.to(dev), w.to(dev)
+        st = dict(op=op, x=xd, w=wd)
+        st["y_ref"] = qmm.reference_gemm(xd.unsqueeze(0), wd.unsqueeze(0))
+        st["dx"] = torch.empty(1, dtype=torch.float32, device=dev); st["dw"] = torch.empty(1, dtype=torch.float32, device=dev)
+        st["cx"] = torch.empty((1, op.M, op.K), dtype=torch.uint8, device=dev)
+        st["cw"] = torch.empty((1, op.N, op.K), dtype=torch.uint8, device=dev)
+        st["y"] = torch.empty((1, op.M, op.N), dtype=torch.bfloat16, device=dev)
+        st["m"] = torch.empty(16, dtype=torch.float64, device=dev)
+        st["ws"] = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
+        st["host_x"], st["host_w"] = x, w
+        state.append(st)
+    torch.cuda.synchronize()
+
+    kinds = ("scale", "quantize", "gemm", "metric")
+    events = {k: [] for k in kinds}
+
+    def timed(kind, record, fn):
+        if record:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); fn(); e1.record()
+            events[kind].append((e0, e1))
+        else:
+            fn()
+
+    def step(record):
+        for st in state:
+            op = st["op"]
+            timed("scale", record, lambda: (qmm.scale(st["x"], 1, fmt, out=st["dx"], workspace=st["ws"]),
+                                            qmm.scale(st["w"], 1, fmt, out=st["dw"], workspace=st["ws"])))
+            timed("quantize", record, lambda: (qmm.quantize(st["x"], 1, fmt, st["dx"], out=st["cx"]),
+                                               qmm.quantize(st["w"], 1, fmt, st["dw"], out=st["cw"])))
+            oa = qmm.operand(st["cx"], fmt, st["dx"]); ob = qmm.operand(st["cw"], fmt, st["dw"])
+            timed("gemm", record, lambda: qmm.gemm((st["cx"], oa), (st["cw"], ob), out=st["y"]))
+            timed("metric", record, lambda: qmm.metric(st["y"], st["y_ref"], out=st["m"], workspace=st["ws"]))
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    flops = sum(op.flops for op in ops)
+    ms_per_step = dt / args.steps * 1e3
+    value = flops / (dt / args.steps) / 1e12
+
+    # ---- per-kernel-class device time from HIP events on the launch stream
+    per_kind_ms = {k: sum(a.elapsed_time(b) for a, b in v) / args.steps for k, v in events.items()}
+    elems_x = sum(op.M * op.K for op in ops); elems_w = sum(op.N * op.K for op in ops); elems_y = sum(op.M * op.N for op in ops)
+    algo_bytes = {"scale": 2 * (elems_x + elems_w), "quantize": 3 * (elems_x + elems_w),
+                  "metric": (2 + 4) * elems_y}
+    gemm_ms_per_launch = per_kind_ms["gemm"] / len(ops)
+    gemm_tflops = flops / (per_kind_ms["gemm"] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_kernel (fp8/int8 MFMA, 4 launches per step)",
+                "achieved": round(gemm_tflops, 1), "peak": PEAK[args.format], "unit": "TFLOP/s",
+                "frac": round(gemm_tflops / PEAK[args.format], 4), "traffic": None,
+                "avg_launch_ms": round(gemm_ms_per_launch, 4)}
+    passes = {k: {"ms_per_step": round(per_kind_ms[k], 4),
+                  "GBps": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9, 1),
+                  "frac_hbm": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+              for k in ("scale", "quantize", "metric")}
+    nsr = {st["op"].name: float(st["m"][0].item() / st["m"][1].item()) for st in state}
+
+    # ---- the oracle timed on the host cores, on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(state, args.format)
+
+    out = {"metric": "quantized GEMM TFLOP/s (e4m3/int8) + metric-pass GB/s, % of MI355X peak",
+           "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": {"e4m3": "fp8_e4m3", "e5m2": "fp8_e5m2", "int8": "int8"}[args.format], "data": "synthetic",
+           "config": {"workload": f"{args.workload}: scale+quantize+gemm+descale+metric over QKV, attn_out, FFN1, FFN2 "
+                                  f"(tokens {dims['tokens']}, hidden {dims['hidden']}, ffn {dims['ffn']}), "
+                                  f"{args.format} per-tensor, bf16 out, reference product precomputed",
+                      "flops_per_step": flops},
+           "roofline": roofline, "passes": passes, "gemm_tflops": round(gemm_tflops, 1), "nsr": nsr,
+           "cpu_baseline": cpu}
+    print(json.dumps(out))
+
+
+def cpu_baseline(state, fmt_name, rows_per_op=256):
+    """Time the oracle (as it stands) on `rows_per_op` seeded rows of every op: scale and quantize of those rows of X
+    and of all of W, the product of those rows with all of W, descale and metric."""
+    import numpy as np
+    from oracle import oracle as O
+    fmt = O.FORMATS[fmt_name]
+    O.lib()
+    flops = 0
+    t0 = time.perf_counter()
+    for st in state:
+        op = st["op"]
+        rng = np.random.default_rng(op.M + op.N)
+        rows = np.sort(rng.choice(op.M, size=min(rows_per_op, op.M), replace=False))
+        xs = st["host_x"][torch_index(rows)].float().numpy()
+        w = st["host_w"].float().numpy()
+        dx = O.scale(xs, 1, fmt); dw = O.scale(w, 1, fmt)
+        cx = O.quantize(xs, 1, fmt, dx); cw = O.quantize(w, 1, fmt, dw)
+        acc = O.gemm_codes(cx, fmt, cw, fmt, want_sabs=False)
+        y = O.dequant(acc, dx, dw, out_bf16=True)
+        r = O.ref_gemm(xs, w)
+        O.metric(y, r)
+        flops += 2 * len(rows) * op.N * op.K
+    dt = time.perf_counter() - t0
+    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": f"{rows_per_op} seeded rows of X per op against all of W (4 ops), full path incl. reference product; "
+                      f"{dt:.1f} s of CPU work"}
+
+
+def torch_index(rows):
+    import torch
+    return torch.from_numpy(rows)
+
+
+if __name__ == "__main__":
+    main()

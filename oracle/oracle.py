@@ -43,6 +43,7 @@ def lib():
         L = ctypes.CDLL(_LIB)
         i64, u64, i32, u32 = ctypes.c_int64, ctypes.c_uint64, ctypes.c_int, ctypes.c_uint32
         vp, f32, f64 = ctypes.c_void_p, ctypes.c_float, ctypes.c_double
+        L.orc_num_threads.restype = i32; L.orc_num_threads.argtypes = []
         L.orc_qmax.restype = f64; L.orc_qmax.argtypes = [i32]
         L.orc_fp8_value.restype = f64; L.orc_fp8_value.argtypes = [i32, ctypes.c_uint]
         L.orc_code_value.restype = f64; L.orc_code_value.argtypes = [i32, ctypes.c_uint]
@@ -81,6 +82,10 @@ def _f32_3d(x):
         x = x[None]
     assert x.ndim == 3
     return x
+
+
+def num_threads():
+    return lib().orc_num_threads()
 
 
 def qmax(fmt):

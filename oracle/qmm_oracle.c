@@ -31,8 +31,22 @@
 #include <stdlib.h>
 #include <string.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
 enum { ORC_INT8 = 0, ORC_E4M3 = 1, ORC_E5M2 = 2 };
 enum { ORC_RTNE = 0, ORC_STOCHASTIC = 1 };
+
+/* Threads the row-parallel loops of the products use (for reporting). */
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* ------------------------------------------------------------------ */
 /* Formats                                                             */

@@ -134,8 +134,10 @@ def quantize(x, contract_axis, fmt, delta, per_channel=False, batch_groups=1, mo
 
 def operand(data, fmt, delta=None, per_channel=False, batch_groups=1, is_codes=True):
     assert data.is_contiguous()
-    return Operand(data.data_ptr(), fmt, int(is_codes), delta.data_ptr() if delta is not None else None,
-                   granularity(per_channel, batch_groups))
+    op = Operand(data.data_ptr(), fmt, int(is_codes), delta.data_ptr() if delta is not None else None,
+                 granularity(per_channel, batch_groups))
+    op._keep = (data, delta)   # the struct holds raw device pointers: keep their owners alive with it
+    return op
 
 
 def gemm(a, b, out_dtype=torch.float32, want_acc=False, out=None, acc_out=None, want_y=True):
