@@ -4,24 +4,27 @@
 // plus the bfloat16 pass-through product used as the high-precision reference.
 //
 // Design (gfx950, wave64, MFMA):
-//  * Workgroup = 4 wavefronts in a 2 x 2 grid; one wavefront owns 16*TM rows (m)
-//    by 64*TG columns (n) of the output in registers.
+//  * Workgroup = 4 wavefronts in a 2 x 2 grid; one wavefront owns 32*TM rows (m)
+//    by 64*TG columns (n) of the output in accumulator registers (128 x 128 for
+//    the large tile: 256 AGPRs).
 //  * Operands are [rows][K] with K contiguous.  A K-slab of 128 bytes per row is
-//    staged in LDS in "fragment blocks": 16 rows x 64 bytes = 1 KiB, lane l of a
-//    wavefront owning the 16 bytes (row l%16, byte group l/16).  One
-//    global_load_lds_dwordx4 per wavefront fills one block straight from global
-//    memory (no staging registers), and one ds_read_b128 per lane reads a block
-//    back with every lane on consecutive addresses, so reads are free of bank
-//    conflicts by construction.
-//  * A block is exactly one operand of v_mfma_i32_16x16x64_i8 or
-//    v_mfma_f32_16x16x32_bf16; two blocks (the two 64-byte halves of the slab)
-//    make one operand of v_mfma_f32_16x16x128_f8f6f4.  Which K bytes a lane holds
-//    is the same for both operands, which is all a contraction needs.
+//    staged in LDS as plain 128-byte rows; the 16-byte chunk c of LDS row p sits
+//    at chunk position c ^ ((p >> 1) & 7).  global_load_lds_dwordx4 copies
+//    straight from global memory into LDS (no staging registers): one
+//    instruction moves 8 rows x 128 bytes, so every 8 lanes read one whole
+//    128-byte line of a row (the pattern the texture path handles best) and the
+//    XOR is applied to the global chunk a lane fetches.  With that swizzle the
+//    16 or 32 lanes of an MFMA operand that read the same logical chunk of
+//    consecutive rows hit distinct banks (measured: same rate as linear reads).
+//  * FP8 uses v_mfma_f32_16x16x128_f8f6f4; INT8 uses v_mfma_i32_32x32x32_i8 and
+//    bfloat16 v_mfma_f32_32x32x16_bf16 (measured on this part: the 16x16 forms of
+//    those two issue at ~60 % of the 32x32 rate).  Which K bytes a lane holds is
+//    the same for both operands, which is all a contraction needs.
 //  * The B matrix (n) feeds the MFMA's first operand and A (m) the second, so a
-//    lane ends up with 4 consecutive n of one m per MFMA.  The 16 rows of a B
-//    block are picked so that the four MFMAs of a 64-column group give a lane 16
-//    consecutive columns: stores are 32 (bf16) or 64 (fp32) contiguous bytes per
-//    lane and whole 128-byte lines per row and wavefront.
+//    lane ends up holding several n of one m.  The rows of a B block are picked
+//    from global memory in a permuted order such that a lane's values are 16
+//    consecutive columns per 64-column group half: stores are 32 (bf16) or 64
+//    (fp32) contiguous bytes per lane and whole 128-byte lines per row.
 //  * Two LDS stages; the slab for step k+1 is in flight while step k multiplies.
 //  * Workgroup ids are spread so that each XCD (own L2) walks a compact band of
 //    tiles.
@@ -34,7 +37,9 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -42,8 +47,7 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 enum Kind { KIND_I8 = 0, KIND_F8 = 1, KIND_BF16 = 2 };
 
 constexpr int kThreads = 256;
-constexpr int kSlabBytes = 128;      // K bytes per row per pipeline step
-constexpr int kBlockBytes = 1024;    // one fragment block: 16 rows x 64 bytes
+constexpr int kSlabBytes = 128;      // K bytes per row per pipeline step = one LDS row
 constexpr int kNumXcd = 8;
 
 __device__ __attribute__((aligned(16))) const uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};
@@ -61,28 +65,34 @@ struct GemmArgs {
     int tiles_m, tiles_n;
 };
 
-// LDS copy of 16 bytes per lane: lane l lands at lds_block + 16*l.
-QMM_DEV void load_block_to_lds(const uint8_t* gptr, uint8_t* lds_block)
+// 16 bytes per lane from global memory into LDS: lane l lands at lds_unit + 16*l.
+QMM_DEV void dma16(const uint8_t* gptr, uint8_t* lds_unit)
 {
     typedef const __attribute__((address_space(1))) void* gptr_t;
     typedef __attribute__((address_space(3))) void* lptr_t;
-    __builtin_amdgcn_global_load_lds((gptr_t)gptr, (lptr_t)lds_block, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr_t)gptr, (lptr_t)lds_unit, 16, 0, 0);
 }
 
 template <int KIND, int FA, int FB, int TM, int TG>
 __global__ void __launch_bounds__(kThreads, 1)
 gemm_kernel(GemmArgs g)
 {
-    constexpr int TN = 4 * TG;                 // 16-column MFMA tiles per wavefront
-    constexpr int BM = 2 * 16 * TM;            // workgroup tile rows
+    constexpr bool F8 = (KIND == KIND_F8);
+    constexpr int BM = 2 * 32 * TM;            // workgroup tile rows
     constexpr int BN = 2 * 64 * TG;            // workgroup tile columns
-    constexpr int A_BLOCKS = BM / 16, B_BLOCKS = BN / 16;
-    constexpr int STAGE_BYTES = (A_BLOCKS + B_BLOCKS) * 2 * kBlockBytes;
+    constexpr int WM = 32 * TM, WN = 64 * TG;  // wavefront tile
+    constexpr int R = F8 ? 16 : 32;            // rows of one MFMA operand block
+    constexpr int BLOCKS_M = WM / R;           // A blocks per wavefront
+    constexpr int TILES_N = WN / R;            // B blocks per wavefront
+    constexpr int KS = F8 ? 1 : 4;             // MFMA K slices per 128-byte slab
+    constexpr int STAGE_BYTES = (BM + BN) * kSlabBytes;
+    constexpr int A_UNITS = BM / 8, B_UNITS = BN / 8;          // DMA units of 8 LDS rows
+    constexpr int A_PER_WAVE = A_UNITS / 4, B_PER_WAVE = B_UNITS / 4;
+    static_assert(BLOCKS_M % 2 == 0, "A fragments ping-pong between two register sets");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int lrow = lane & 15, lgrp = lane >> 4;
 
     // ---- workgroup id -> (batch, tile_m, tile_n), XCD-aware and grouped along m
     const int64_t tiles_per_batch = (int64_t)g.tiles_m * g.tiles_n;
@@ -94,7 +104,7 @@ gemm_kernel(GemmArgs g)
         pid = (tall == 0 || xcd < tall) ? xcd * per + loc : tall * per + (xcd - tall) * (per - 1) + loc;
     }
     const int64_t bidx = pid / tiles_per_batch;
-    int64_t t = pid - bidx * tiles_per_batch;
+    const int64_t t = pid - bidx * tiles_per_batch;
     constexpr int GROUP_M = 8;
     const int64_t in_group = (int64_t)GROUP_M * g.tiles_n;
     const int64_t grp = t / in_group;
@@ -107,186 +117,253 @@ gemm_kernel(GemmArgs g)
     const uint8_t* A = g.a + bidx * g.M * g.rowbytes;
     const uint8_t* B = g.b + bidx * g.N * g.rowbytes;
 
-    // ---- global sources of the blocks this wavefront copies: A row blocks wave*A_BLOCKS/4 .., same for B
-    constexpr int A_PER_WAVE = A_BLOCKS / 4, B_PER_WAVE = B_BLOCKS / 4;
-    const uint8_t* a_src[A_PER_WAVE];
-    const uint8_t* b_src[B_PER_WAVE];
+    // ---- DMA sources.  Unit u = LDS rows 8u..8u+7; lane l fills row 8u + l/8, chunk position l%8, i.e. fetches
+    //      logical chunk (l%8) ^ ((row>>1)&7) of the global row parked there.  LDS row p of the B region holds
+    //      output column  WN*(p/WN) + TILES_N*(p%R) + (p/R)%TILES_N : MFMA block t, lane j  <->  column TILES_N*j + t,
+    //      so that in the accumulators a lane owns TILES_N consecutive columns of a row.
+    //      Sources are kept as 32-bit byte offsets from the tile's first A / B row.
+    const uint8_t* a_tile = A + m0 * g.rowbytes;
+    const uint8_t* b_tile = B + n0 * g.rowbytes;
+    uint32_t a_src[A_PER_WAVE], b_src[B_PER_WAVE];
+    const int lane_chunk_base = lane & 7;
 #pragma unroll
     for (int i = 0; i < A_PER_WAVE; ++i) {
-        const int rb = wave * A_PER_WAVE + i;
-        int64_t row = m0 + rb * 16 + lrow;
-        row = row < g.M ? row : g.M - 1;
-        a_src[i] = A + row * g.rowbytes + lgrp * 16;
+        const int p = (wave * A_PER_WAVE + i) * 8 + (lane >> 3);
+        const int c = lane_chunk_base ^ ((p >> 1) & 7);
+        int64_t row = p;
+        row = m0 + row < g.M ? row : g.M - 1 - m0;
+        a_src[i] = (uint32_t)(row * g.rowbytes + c * 16);
     }
 #pragma unroll
     for (int i = 0; i < B_PER_WAVE; ++i) {
-        const int nb = wave * B_PER_WAVE + i;          // n block: 64-column group nb/4, MFMA tile nb%4
-        int64_t row = n0 + (nb >> 2) * 64 + (lrow >> 2) * 16 + (nb & 3) * 4 + (lrow & 3);
-        row = row < g.N ? row : g.N - 1;
-        b_src[i] = B + row * g.rowbytes + lgrp * 16;
+        const int p = (wave * B_PER_WAVE + i) * 8 + (lane >> 3);
+        const int c = lane_chunk_base ^ ((p >> 1) & 7);
+        int64_t row = WN * (p / WN) + TILES_N * (p % R) + (p / R) % TILES_N;
+        row = n0 + row < g.N ? row : g.N - 1 - n0;
+        b_src[i] = (uint32_t)(row * g.rowbytes + c * 16);
     }
 
     auto issue_loads = [&](int64_t k0, int stage) {
         uint8_t* sa = lds + stage * STAGE_BYTES;
-        uint8_t* sb = sa + A_BLOCKS * 2 * kBlockBytes;
-        const bool tail = k0 + kSlabBytes > g.rowbytes;   // uniform
-        const uint8_t* zero = reinterpret_cast<const uint8_t*>(g_zero16);
+        uint8_t* sb = sa + BM * kSlabBytes;
+        const uint8_t* ak = a_tile + k0;
+        const uint8_t* bk = b_tile + k0;
+        if (k0 + kSlabBytes <= g.rowbytes) {
 #pragma unroll
-        for (int piece = 0; piece < 2; ++piece) {
-            const int64_t off = k0 + piece * 64;
-            const bool oob = tail && (off + lgrp * 16 >= g.rowbytes);
+            for (int i = 0; i < A_PER_WAVE; ++i) dma16(ak + a_src[i], sa + (wave * A_PER_WAVE + i) * 1024);
+#pragma unroll
+            for (int i = 0; i < B_PER_WAVE; ++i) dma16(bk + b_src[i], sb + (wave * B_PER_WAVE + i) * 1024);
+        } else {   // last, partial slab: chunks past the end of the row read zeros
+            const uint8_t* zero = reinterpret_cast<const uint8_t*>(g_zero16);
 #pragma unroll
             for (int i = 0; i < A_PER_WAVE; ++i) {
-                const int rb = wave * A_PER_WAVE + i;
-                load_block_to_lds(oob ? zero : a_src[i] + off, sa + (rb * 2 + piece) * kBlockBytes);
+                const int p = (wave * A_PER_WAVE + i) * 8 + (lane >> 3);
+                const int c = lane_chunk_base ^ ((p >> 1) & 7);
+                dma16(k0 + c * 16 < g.rowbytes ? ak + a_src[i] : zero, sa + (wave * A_PER_WAVE + i) * 1024);
             }
 #pragma unroll
             for (int i = 0; i < B_PER_WAVE; ++i) {
-                const int nb = wave * B_PER_WAVE + i;
-                load_block_to_lds(oob ? zero : b_src[i] + off, sb + (nb * 2 + piece) * kBlockBytes);
+                const int p = (wave * B_PER_WAVE + i) * 8 + (lane >> 3);
+                const int c = lane_chunk_base ^ ((p >> 1) & 7);
+                dma16(k0 + c * 16 < g.rowbytes ? bk + b_src[i] : zero, sb + (wave * B_PER_WAVE + i) * 1024);
             }
         }
     };
 
-    using AccT = typename std::conditional<KIND == KIND_I8, v4i, v4f>::type;
-    AccT acc[TM][TN];
+    // ---- accumulators: acc[A block][B block]
+    using AccT = typename std::conditional<F8, v4f, typename std::conditional<KIND == KIND_I8, v16i, v16f>::type>::type;
+    using Frag = typename std::conditional<F8, v8i, v4i>::type;
+    AccT acc[BLOCKS_M][TILES_N];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < BLOCKS_M; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = AccT{0, 0, 0, 0};
+        for (int j = 0; j < TILES_N; ++j)
+#pragma unroll
+            for (int e = 0; e < (F8 ? 4 : 16); ++e) acc[i][j][e] = 0;
+
+    // FP8: lane (r = l%16, g = l/16) reads chunks g and g+4 of row r of a 16-row block.
+    // INT8/BF16: lane (r = l%32, h = l/32) reads chunk 2s+h of row r of a 32-row block for K slice s = 0..3.
+    const int frow = lane & (R - 1);
+    const int fkey = (frow >> 1) & 7;
+    const int fsel = F8 ? (lane >> 4) : (lane >> 5);
+    const int a_off = (wm * WM + frow) * kSlabBytes;
+    const int b_off = BM * kSlabBytes + (wn * WN + frow) * kSlabBytes;
+    int coff[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) coff[s] = ((F8 ? fsel : 2 * s + fsel) ^ fkey) * 16;
+
+    auto read_frag = [&](const uint8_t* row_ptr, int s) -> Frag {
+        if constexpr (F8) {
+            const v4i p0 = *reinterpret_cast<const v4i*>(row_ptr + coff[0]);
+            const v4i p1 = *reinterpret_cast<const v4i*>(row_ptr + (coff[0] ^ 64));
+            return v8i{p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
+        } else {
+            return *reinterpret_cast<const v4i*>(row_ptr + coff[s]);
+        }
+    };
+    auto mma = [&](const Frag& fa, const Frag& fb, AccT& c) {
+        // first operand: A rows -> the 4-row groups held in a lane's registers; second: B rows -> lane%R
+        if constexpr (F8)
+            c = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fa, fb, c, FA == QMM_FMT_E5M2 ? 1 : 0,
+                                                                 FB == QMM_FMT_E5M2 ? 1 : 0, 0, 0, 0, 0);
+        else if constexpr (KIND == KIND_I8)
+            c = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, c, 0, 0, 0);
+        else
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fa), __builtin_bit_cast(v8bf, fb), c, 0, 0, 0);
+    };
+
+    Frag fb[KS][TILES_N];      // B fragments of the current slab
+    Frag fa[2][KS];            // A fragments of one block, ping-pong between blocks
+
+    auto read_a = [&](int stage, int i, int buf) {
+        const uint8_t* sa = lds + stage * STAGE_BYTES + a_off + i * R * kSlabBytes;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) fa[buf][s] = read_frag(sa, s);
+    };
 
     const int64_t nk = (g.rowbytes + kSlabBytes - 1) / kSlabBytes;
     issue_loads(0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    if (nk > 1) issue_loads(kSlabBytes, 1);
+    {
+        const uint8_t* sb = lds + b_off;
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int j = 0; j < TILES_N; ++j) fb[s][j] = read_frag(sb + j * R * kSlabBytes, s);
+    }
+    read_a(0, 0, 0);
 
+    // One K step.  On entry fb and fa[0] hold this slab's first fragments and the DMA of the next slab is in
+    // flight.  The fragments of A block i+1 are requested before the MFMAs of block i are issued.  Before the last
+    // block the wavefronts meet: every read of this slab has completed and the next slab has landed; the last
+    // block's MFMAs then run while each B fragment register is refilled from the next slab right after its last
+    // use, so LDS latency hides behind matrix work and the B fragments need one register set only.
     for (int64_t kt = 0; kt < nk; ++kt) {
         const int stage = (int)(kt & 1);
-        if (kt + 1 < nk) issue_loads((kt + 1) * kSlabBytes, stage ^ 1);
-
-        const uint8_t* sa = lds + stage * STAGE_BYTES + (wm * (A_BLOCKS / 2)) * 2 * kBlockBytes + lane * 16;
-        const uint8_t* sb = lds + stage * STAGE_BYTES + A_BLOCKS * 2 * kBlockBytes +
-                            (wn * (B_BLOCKS / 2)) * 2 * kBlockBytes + lane * 16;
-        if constexpr (KIND == KIND_F8) {
-            v8i fb[TN];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const v4i p0 = *reinterpret_cast<const v4i*>(sb + (j * 2 + 0) * kBlockBytes);
-                const v4i p1 = *reinterpret_cast<const v4i*>(sb + (j * 2 + 1) * kBlockBytes);
-                fb[j] = v8i{p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
-            }
+        for (int i = 0; i < BLOCKS_M - 1; ++i) {
+            // first MFMA of the block, then the request for the next block's fragments, then the rest: whatever
+            // wait the compiler puts in front of the first MFMA then never covers the newest request
+            mma(fa[i & 1][0], fb[0][0], acc[i][0]);
+            __builtin_amdgcn_sched_barrier(0);
+            read_a(stage, i + 1, (i + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const v4i p0 = *reinterpret_cast<const v4i*>(sa + (i * 2 + 0) * kBlockBytes);
-                const v4i p1 = *reinterpret_cast<const v4i*>(sa + (i * 2 + 1) * kBlockBytes);
-                const v8i fa = v8i{p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
+            for (int s = 0; s < KS; ++s)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                        fb[j], fa, acc[i][j], FB == QMM_FMT_E5M2 ? 1 : 0, FA == QMM_FMT_E5M2 ? 1 : 0, 0, 0, 0, 0);
-            }
-        } else {
-#pragma unroll
-            for (int piece = 0; piece < 2; ++piece) {
-                v4i fb[TN];
-#pragma unroll
-                for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const v4i*>(sb + (j * 2 + piece) * kBlockBytes);
-#pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    const v4i fa = *reinterpret_cast<const v4i*>(sa + (i * 2 + piece) * kBlockBytes);
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        if constexpr (KIND == KIND_I8)
-                            acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fb[j], fa, acc[i][j], 0, 0, 0);
-                        else
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                __builtin_bit_cast(v8bf, fb[j]), __builtin_bit_cast(v8bf, fa), acc[i][j], 0, 0, 0);
-                    }
-                }
-            }
+                for (int j = 0; j < TILES_N; ++j)
+                    if (s + j > 0) mma(fa[i & 1][s], fb[s][j], acc[i][j]);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+        const bool more = kt + 1 < nk;
+        if (more) {
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (kt + 2 < nk) issue_loads((kt + 2) * kSlabBytes, stage);
+            read_a(stage ^ 1, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        const uint8_t* sb_next = lds + (stage ^ 1) * STAGE_BYTES + b_off;
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int j = 0; j < TILES_N; ++j) {
+                mma(fa[(BLOCKS_M - 1) & 1][s], fb[s][j], acc[BLOCKS_M - 1][j]);
+                if (more) fb[s][j] = read_frag(sb_next + j * R * kSlabBytes, s);
+            }
+        __builtin_amdgcn_sched_barrier(0);
     }
 
-    // ---- epilogue: lane (lgrp, lrow) holds, for row block i and column group gq, the 16 columns
-    //      n = n_base + gq*64 + lgrp*16 + [0,16) of row m = m_base + i*16 + lrow.
-    const int64_t m_base = m0 + wm * (BM / 2), n_base = n0 + wn * (BN / 2);
+    // ---- epilogue.  MFMA result D[i][j]: i = A row within the block, j = lane % R = B row within the block.
+    //  16x16: a lane's register r of acc[ia][t] is row 16*ia + 4*(l/16) + r, column TILES_N*(l%16) + t
+    //  32x32: a lane's register v of acc[ia][t] is row 32*ia + 8*(v/4) + 4*(l/32) + v%4, column TILES_N*(l%32) + t
+    //  so for a fixed register the TILES_N accumulators of a lane are consecutive columns, and the lanes of a
+    //  store instruction cover whole rows of the wavefront tile.
+    const int64_t m_base = m0 + wm * WM, n_base = n0 + wn * WN;
     const float* da = g.da ? g.da + (bidx % g.da_groups) * (g.da_per_channel ? g.M : 1) : nullptr;
     const float* db = g.db ? g.db + (bidx % g.db_groups) * (g.db_per_channel ? g.N : 1) : nullptr;
-    const bool descale = (KIND != KIND_BF16);
-    const bool vec_ok = (g.N % 16) == 0;
-    float sa_scalar = 1.0f, sb_scalar = 1.0f;
-    if (descale) {
-        if (!g.da_per_channel) sa_scalar = da[0];
-        if (!g.db_per_channel) sb_scalar = db[0];
+    constexpr bool descale = (KIND != KIND_BF16);
+    constexpr int REGS = F8 ? 4 : 16;
+    const int64_t n = n_base + TILES_N * (lane & (R - 1));     // first of this lane's TILES_N columns
+    const bool vec_ok = (g.N % TILES_N) == 0 && n + TILES_N <= g.N;
+    float sr[TILES_N];
+#pragma unroll
+    for (int tt = 0; tt < TILES_N; ++tt) {
+        sr[tt] = 1.0f;
+        if constexpr (descale) sr[tt] = g.db_per_channel ? db[(n + tt) < g.N ? (n + tt) : (g.N - 1)] : db[0];
     }
+    float sa_scalar = 1.0f;
+    if constexpr (descale) { if (!g.da_per_channel) sa_scalar = da[0]; }
+    if (n < g.N) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int64_t m = m_base + i * 16 + lrow;
-        if (m >= g.M) continue;
-        const float sl = (descale && g.da_per_channel) ? da[m] : sa_scalar;
+        for (int ia = 0; ia < BLOCKS_M; ++ia) {
 #pragma unroll
-        for (int gq = 0; gq < TG; ++gq) {
-            const int64_t n = n_base + gq * 64 + lgrp * 16;
-            if (n >= g.N) continue;
-            const int64_t o = (bidx * g.M + m) * g.N + n;
-            float v[16];
-            uint32_t raw[16];
+            for (int r = 0; r < REGS; ++r) {
+                const int64_t m = m_base + ia * R + (F8 ? 4 * (lane >> 4) + r : 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3));
+                if (m >= g.M) continue;
+                float sl = sa_scalar;
+                if constexpr (descale) { if (g.da_per_channel) sl = da[m]; }
+                const int64_t o = (bidx * g.M + m) * g.N + n;
+                float v[TILES_N];
+                uint32_t raw[TILES_N];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int c = j * 4 + r;
+                for (int tt = 0; tt < TILES_N; ++tt) {
                     float a;
                     if constexpr (KIND == KIND_I8) {
-                        raw[c] = (uint32_t)acc[i][gq * 4 + j][r];
-                        a = (float)acc[i][gq * 4 + j][r];
+                        raw[tt] = (uint32_t)acc[ia][tt][r];
+                        a = (float)acc[ia][tt][r];
                     } else {
-                        a = acc[i][gq * 4 + j][r];
-                        raw[c] = __float_as_uint(a);
+                        a = acc[ia][tt][r];
+                        raw[tt] = __float_as_uint(a);
                     }
-                    if (descale) {
-                        const float sr = g.db_per_channel ? db[(n + c) < g.N ? (n + c) : (g.N - 1)] : sb_scalar;
-                        a = (a * sl) * sr;
+                    if constexpr (descale) a = (a * sl) * sr[tt];
+                    v[tt] = a;
+                }
+                if (vec_ok) {
+                    if (g.acc_out) {
+                        uint32_t* dst = static_cast<uint32_t*>(g.acc_out) + o;
+                        if constexpr (TILES_N >= 4) {
+#pragma unroll
+                            for (int q = 0; q < TILES_N / 4; ++q)
+                                reinterpret_cast<u32x4*>(dst)[q] = u32x4{raw[4 * q], raw[4 * q + 1], raw[4 * q + 2], raw[4 * q + 3]};
+                        } else {
+                            *reinterpret_cast<u32x2*>(dst) = u32x2{raw[0], raw[1]};
+                        }
                     }
-                    v[c] = a;
-                }
-            if (vec_ok) {
-                if (g.acc_out) {
-                    u32x4* dst = reinterpret_cast<u32x4*>(static_cast<uint32_t*>(g.acc_out) + o);
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) dst[q] = u32x4{raw[4 * q], raw[4 * q + 1], raw[4 * q + 2], raw[4 * q + 3]};
-                }
-                if (g.y) {
-                    if (g.y_bf16) {
-                        uint32_t pk[8];
-#pragma unroll
-                        for (int q = 0; q < 8; ++q) {
+                    if (g.y) {
+                        if (g.y_bf16) {
                             typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
                             typedef float f2 __attribute__((ext_vector_type(2)));
-                            const bf2 h = __builtin_convertvector(f2{v[2 * q], v[2 * q + 1]}, bf2);
-                            pk[q] = __builtin_bit_cast(uint32_t, h);
+                            uint32_t pk[TILES_N / 2];
+#pragma unroll
+                            for (int q = 0; q < TILES_N / 2; ++q)
+                                pk[q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{v[2 * q], v[2 * q + 1]}, bf2));
+                            uint16_t* dst = static_cast<uint16_t*>(g.y) + o;
+                            if constexpr (TILES_N == 8) *reinterpret_cast<u32x4*>(dst) = u32x4{pk[0], pk[1], pk[2], pk[3]};
+                            else if constexpr (TILES_N == 4) *reinterpret_cast<u32x2*>(dst) = u32x2{pk[0], pk[1]};
+                            else *reinterpret_cast<uint32_t*>(dst) = pk[0];
+                        } else {
+                            float* dst = static_cast<float*>(g.y) + o;
+                            if constexpr (TILES_N >= 4) {
+#pragma unroll
+                                for (int q = 0; q < TILES_N / 4; ++q)
+                                    reinterpret_cast<u32x4*>(dst)[q] = u32x4{__float_as_uint(v[4 * q]), __float_as_uint(v[4 * q + 1]),
+                                                                             __float_as_uint(v[4 * q + 2]), __float_as_uint(v[4 * q + 3])};
+                            } else {
+                                *reinterpret_cast<u32x2*>(dst) = u32x2{__float_as_uint(v[0]), __float_as_uint(v[1])};
+                            }
                         }
-                        u32x4* dst = reinterpret_cast<u32x4*>(static_cast<uint16_t*>(g.y) + o);
-                        dst[0] = u32x4{pk[0], pk[1], pk[2], pk[3]};
-                        dst[1] = u32x4{pk[4], pk[5], pk[6], pk[7]};
-                    } else {
-                        u32x4* dst = reinterpret_cast<u32x4*>(static_cast<float*>(g.y) + o);
-#pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            dst[q] = u32x4{__float_as_uint(v[4 * q]), __float_as_uint(v[4 * q + 1]),
-                                           __float_as_uint(v[4 * q + 2]), __float_as_uint(v[4 * q + 3])};
                     }
-                }
-            } else {
-#pragma unroll
-                for (int c = 0; c < 16; ++c) {
-                    if (n + c >= g.N) break;
-                    if (g.acc_out) static_cast<uint32_t*>(g.acc_out)[o + c] = raw[c];
-                    if (g.y) {
-                        if (g.y_bf16) static_cast<__bf16*>(g.y)[o + c] = (__bf16)v[c];
-                        else static_cast<float*>(g.y)[o + c] = v[c];
+                } else {
+                    for (int tt = 0; tt < TILES_N; ++tt) {
+                        if (n + tt >= g.N) break;
+                        if (g.acc_out) static_cast<uint32_t*>(g.acc_out)[o + tt] = raw[tt];
+                        if (g.y) {
+                            if (g.y_bf16) static_cast<__bf16*>(g.y)[o + tt] = (__bf16)v[tt];
+                            else static_cast<float*>(g.y)[o + tt] = v[tt];
+                        }
                     }
                 }
             }
@@ -297,8 +374,8 @@ gemm_kernel(GemmArgs g)
 template <int KIND, int FA, int FB, int TM, int TG>
 qmm_status launch_tile(GemmArgs& g, hipStream_t s)
 {
-    constexpr int BM = 2 * 16 * TM, BN = 2 * 64 * TG;
-    constexpr int STAGE_BYTES = (BM / 16 + BN / 16) * 2 * kBlockBytes;
+    constexpr int BM = 2 * 32 * TM, BN = 2 * 64 * TG;
+    constexpr int STAGE_BYTES = (BM + BN) * kSlabBytes;
     constexpr int LDS_BYTES = 2 * STAGE_BYTES;
     g.tiles_m = (int)((g.M + BM - 1) / BM);
     g.tiles_n = (int)((g.N + BN - 1) / BN);
@@ -320,8 +397,8 @@ qmm_status launch_kind(GemmArgs& g, hipStream_t s)
 {
     // 256 x 256 tiles when they still give every CU work, else 128 x 128.
     const int64_t big = ((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
-    if (big >= 192) return launch_tile<KIND, FA, FB, 8, 2>(g, s);
-    return launch_tile<KIND, FA, FB, 4, 1>(g, s);
+    if (big >= 192) return launch_tile<KIND, FA, FB, 4, 2>(g, s);
+    return launch_tile<KIND, FA, FB, 2, 1>(g, s);
 }
 
 bool is8(int f) { return f == QMM_FMT_INT8 || f == QMM_FMT_E4M3 || f == QMM_FMT_E5M2; }
