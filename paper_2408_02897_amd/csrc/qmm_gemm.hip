@@ -287,7 +287,7 @@ gemm_kernel(GemmArgs g)
     constexpr bool descale = (KIND != KIND_BF16);
     constexpr int REGS = F8 ? 4 : 16;
     const int64_t n = n_base + TILES_N * (lane & (R - 1));     // first of this lane's TILES_N columns
-    const bool vec_ok = (g.N % TILES_N) == 0 && n + TILES_N <= g.N;
+    const int lane_row = F8 ? 4 * (lane >> 4) : 4 * (lane >> 5);
     float sr[TILES_N];
 #pragma unroll
     for (int tt = 0; tt < TILES_N; ++tt) {
@@ -296,77 +296,79 @@ gemm_kernel(GemmArgs g)
     }
     float sa_scalar = 1.0f;
     if constexpr (descale) { if (!g.da_per_channel) sa_scalar = da[0]; }
-    if (n < g.N) {
+
+    // value tt of register r of A block ia, descaled: (acc * deltaA[row]) * deltaB[column], in that order
+    auto value = [&](int ia, int r, int tt, float sl, uint32_t& raw) -> float {
+        float a;
+        if constexpr (BLOCKS_M * TILES_N * REGS >= 256) {
+            // the large tile keeps its 256 accumulators in AGPRs: copy each one out where it is used, so that
+            // the register allocator does not try to hold all of them in VGPRs at once
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(raw) : "a"(acc[ia][tt][r]));
+        } else {
+            if constexpr (KIND == KIND_I8) raw = (uint32_t)acc[ia][tt][r];
+            else raw = __float_as_uint(acc[ia][tt][r]);
+        }
+        if constexpr (KIND == KIND_I8) a = (float)(int32_t)raw;
+        else a = __uint_as_float(raw);
+        if constexpr (descale) a = (a * sl) * sr[tt];
+        return a;
+    };
+    auto row_in_block = [&](int r) -> int { return F8 ? lane_row + r : 8 * (r >> 2) + lane_row + (r & 3); };
+
+    const bool interior = (m0 + BM <= g.M) && (n0 + BN <= g.N) && (g.N % TILES_N == 0);
+    if (interior && g.y && g.y_bf16 && !g.acc_out) {
+        // fast path: whole tile inside the matrix, bfloat16 output only; 2*TILES_N bytes per lane and store
+        uint8_t* ybase = static_cast<uint8_t*>(g.y) + ((bidx * g.M + m_base) * g.N + n) * 2;
+        const int64_t row_bytes = g.N * 2;
 #pragma unroll
         for (int ia = 0; ia < BLOCKS_M; ++ia) {
 #pragma unroll
             for (int r = 0; r < REGS; ++r) {
-                const int64_t m = m_base + ia * R + (F8 ? 4 * (lane >> 4) + r : 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3));
-                if (m >= g.M) continue;
+                const int ml = ia * R + row_in_block(r);
                 float sl = sa_scalar;
-                if constexpr (descale) { if (g.da_per_channel) sl = da[m]; }
-                const int64_t o = (bidx * g.M + m) * g.N + n;
-                float v[TILES_N];
-                uint32_t raw[TILES_N];
+                if constexpr (descale) { if (g.da_per_channel) sl = da[m_base + ml]; }
+                typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+                typedef float f2 __attribute__((ext_vector_type(2)));
+                uint32_t pk[TILES_N / 2];
 #pragma unroll
-                for (int tt = 0; tt < TILES_N; ++tt) {
-                    float a;
-                    if constexpr (KIND == KIND_I8) {
-                        raw[tt] = (uint32_t)acc[ia][tt][r];
-                        a = (float)acc[ia][tt][r];
-                    } else {
-                        a = acc[ia][tt][r];
-                        raw[tt] = __float_as_uint(a);
-                    }
-                    if constexpr (descale) a = (a * sl) * sr[tt];
-                    v[tt] = a;
+                for (int q = 0; q < TILES_N / 2; ++q) {
+                    uint32_t raw0, raw1;
+                    const float v0 = value(ia, r, 2 * q, sl, raw0), v1 = value(ia, r, 2 * q + 1, sl, raw1);
+                    pk[q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{v0, v1}, bf2));
                 }
-                if (vec_ok) {
-                    if (g.acc_out) {
-                        uint32_t* dst = static_cast<uint32_t*>(g.acc_out) + o;
-                        if constexpr (TILES_N >= 4) {
+                uint8_t* dst = ybase + ml * row_bytes;
+                if constexpr (TILES_N == 8) *reinterpret_cast<u32x4*>(dst) = u32x4{pk[0], pk[1], pk[2], pk[3]};
+                else if constexpr (TILES_N == 4) *reinterpret_cast<u32x2*>(dst) = u32x2{pk[0], pk[1]};
+                else *reinterpret_cast<uint32_t*>(dst) = pk[0];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else if (n < g.N) {
+        // general path: edge tiles, float output, raw accumulators; element-wise with bounds checks
 #pragma unroll
-                            for (int q = 0; q < TILES_N / 4; ++q)
-                                reinterpret_cast<u32x4*>(dst)[q] = u32x4{raw[4 * q], raw[4 * q + 1], raw[4 * q + 2], raw[4 * q + 3]};
-                        } else {
-                            *reinterpret_cast<u32x2*>(dst) = u32x2{raw[0], raw[1]};
-                        }
-                    }
-                    if (g.y) {
-                        if (g.y_bf16) {
-                            typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
-                            typedef float f2 __attribute__((ext_vector_type(2)));
-                            uint32_t pk[TILES_N / 2];
+        for (int ia = 0; ia < BLOCKS_M; ++ia) {
 #pragma unroll
-                            for (int q = 0; q < TILES_N / 2; ++q)
-                                pk[q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{v[2 * q], v[2 * q + 1]}, bf2));
-                            uint16_t* dst = static_cast<uint16_t*>(g.y) + o;
-                            if constexpr (TILES_N == 8) *reinterpret_cast<u32x4*>(dst) = u32x4{pk[0], pk[1], pk[2], pk[3]};
-                            else if constexpr (TILES_N == 4) *reinterpret_cast<u32x2*>(dst) = u32x2{pk[0], pk[1]};
-                            else *reinterpret_cast<uint32_t*>(dst) = pk[0];
-                        } else {
-                            float* dst = static_cast<float*>(g.y) + o;
-                            if constexpr (TILES_N >= 4) {
+            for (int r = 0; r < REGS; ++r) {
+                const int64_t m = m_base + ia * R + row_in_block(r);
+                if (m < g.M) {
+                    float sl = sa_scalar;
+                    if constexpr (descale) { if (g.da_per_channel) sl = da[m]; }
+                    const int64_t o = (bidx * g.M + m) * g.N + n;
 #pragma unroll
-                                for (int q = 0; q < TILES_N / 4; ++q)
-                                    reinterpret_cast<u32x4*>(dst)[q] = u32x4{__float_as_uint(v[4 * q]), __float_as_uint(v[4 * q + 1]),
-                                                                             __float_as_uint(v[4 * q + 2]), __float_as_uint(v[4 * q + 3])};
-                            } else {
-                                *reinterpret_cast<u32x2*>(dst) = u32x2{__float_as_uint(v[0]), __float_as_uint(v[1])};
-                            }
-                        }
-                    }
-                } else {
                     for (int tt = 0; tt < TILES_N; ++tt) {
-                        if (n + tt >= g.N) break;
-                        if (g.acc_out) static_cast<uint32_t*>(g.acc_out)[o + tt] = raw[tt];
-                        if (g.y) {
-                            if (g.y_bf16) static_cast<__bf16*>(g.y)[o + tt] = (__bf16)v[tt];
-                            else static_cast<float*>(g.y)[o + tt] = v[tt];
+                        uint32_t raw;
+                        const float v = value(ia, r, tt, sl, raw);
+                        if (n + tt < g.N) {
+                            if (g.acc_out) static_cast<uint32_t*>(g.acc_out)[o + tt] = raw;
+                            if (g.y) {
+                                if (g.y_bf16) static_cast<__bf16*>(g.y)[o + tt] = (__bf16)v;
+                                else static_cast<float*>(g.y)[o + tt] = v;
+                            }
                         }
                     }
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
