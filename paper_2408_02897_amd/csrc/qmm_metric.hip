@@ -15,46 +15,44 @@ constexpr int kMaxBlocks = 2048;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
+// Running sums of one thread.  Branch-free: an element whose error is NaN contributes zeros and bumps nan_cnt.
 struct Acc {
     double s_ee = 0, s_rr = 0, s_ae = 0, s_ar = 0, m_e = 0, m_r = 0;
     double re_sum = 0, re_max = 0, be_sum = 0, be_max = 0;
-    unsigned long long re_cnt = 0, be_cnt = 0, n = 0, nan_cnt = 0;
+    unsigned re_cnt = 0, be_cnt = 0, n = 0, nan_cnt = 0;     // a thread sees far fewer than 2^32 elements
 
     template <bool HAS_D> QMM_DEV void add(float yf, float rf, float df)
     {
         const double e = (double)yf - (double)rf;
-        if (e != e) { ++nan_cnt; return; }
-        const double ae = fabs(e), ar = fabs((double)rf);
-        s_ee = fma(e, e, s_ee);
+        const bool ok = (e == e);
+        const double ae = ok ? fabs(e) : 0.0;
+        const double ar = ok ? fabs((double)rf) : 0.0;
+        s_ee = fma(ae, ae, s_ee);
         s_rr = fma(ar, ar, s_rr);
         s_ae += ae;
         s_ar += ar;
         m_e = fmax(m_e, ae);
         m_r = fmax(m_r, ar);
-        if (ar != 0.0) {
-            const double q = ae / ar;
-            re_sum += q;
-            re_max = fmax(re_max, q);
-            ++re_cnt;
-        }
+        const bool rnz = ar != 0.0;
+        const double q = rnz ? ae / ar : 0.0;                 // Eq. 2 with |v| in the denominator
+        re_sum += q;
+        re_max = fmax(re_max, q);
+        re_cnt += rnz ? 1u : 0u;
         if constexpr (HAS_D) {
             const double d = (double)df;
-            if (d > 0.0) {
-                const double q = ae / d;
-                be_sum += q;
-                be_max = fmax(be_max, q);
-                ++be_cnt;
-            }
+            const bool dpos = ok && d > 0.0;
+            const double qb = dpos ? ae / d : 0.0;            // Eq. 3, element-wise
+            be_sum += qb;
+            be_max = fmax(be_max, qb);
+            be_cnt += dpos ? 1u : 0u;
         }
-        ++n;
+        n += ok ? 1u : 0u;
+        nan_cnt += ok ? 0u : 1u;
     }
 };
 
-// Products e*e and ar*ar are exact in binary64 (24-bit x 24-bit and the error of two binary32 values
-// has at most 49 significant bits... e*e may round); fma keeps one rounding per term, as a plain
-// multiply-then-add would have two.  Either way the comparison tolerance covers it.
-
-QMM_DEV void store_partial(const Acc& a, double* out)
+// Workgroup partials are stored field-major: partial[field * nblocks + block].
+QMM_DEV void store_partial(const Acc& a, double* partial, int nblocks)
 {
     __shared__ double s[kThreads / kWave][16];
     const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
@@ -75,7 +73,18 @@ QMM_DEV void store_partial(const Acc& a, double* out)
         const bool is_max = (i == 4 || i == 5 || i == 7 || i == 10);
         double r = s[0][i];
         for (int k = 1; k < kThreads / kWave; ++k) r = is_max ? fmax(r, s[k][i]) : r + s[k][i];
-        out[i] = r;
+        partial[(int64_t)i * nblocks + blockIdx.x] = r;
+    }
+}
+
+template <bool Y_BF16> QMM_DEV f32x4 load_y4(const void* yv, int64_t i)
+{
+    if constexpr (Y_BF16) {
+        const u32x2 w = reinterpret_cast<const u32x2*>(yv)[i];
+        return f32x4{__uint_as_float(w[0] << 16), __uint_as_float(w[0] & 0xFFFF0000u),
+                     __uint_as_float(w[1] << 16), __uint_as_float(w[1] & 0xFFFF0000u)};
+    } else {
+        return reinterpret_cast<const f32x4*>(yv)[i];
     }
 }
 
@@ -89,20 +98,25 @@ metric_partial(const void* __restrict__ yv, const float* __restrict__ r, const f
     const int64_t tid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const f32x4* r4 = reinterpret_cast<const f32x4*>(r);
     const f32x4* d4 = reinterpret_cast<const f32x4*>(d);
-    for (int64_t i = tid; i < nvec; i += stride) {
-        f32x4 y;
-        if constexpr (Y_BF16) {
-            const u32x2 w = reinterpret_cast<const u32x2*>(yv)[i];
-            y = f32x4{__uint_as_float(w[0] << 16), __uint_as_float(w[0] & 0xFFFF0000u),
-                      __uint_as_float(w[1] << 16), __uint_as_float(w[1] & 0xFFFF0000u)};
-        } else {
-            y = reinterpret_cast<const f32x4*>(yv)[i];
-        }
-        const f32x4 rr = r4[i];
-        f32x4 dd = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (HAS_D) dd = d4[i];
+    int64_t i = tid;
+    // two vectors of four elements per trip: both loads are in flight before the arithmetic of either starts
+    for (; i + stride < nvec; i += 2 * stride) {
+        const f32x4 y0 = load_y4<Y_BF16>(yv, i), y1 = load_y4<Y_BF16>(yv, i + stride);
+        const f32x4 r0 = r4[i], r1 = r4[i + stride];
+        f32x4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (HAS_D) { d0 = d4[i]; d1 = d4[i + stride]; }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc.add<HAS_D>(y[j], rr[j], dd[j]);
+        for (int j = 0; j < 4; ++j) acc.add<HAS_D>(y0[j], r0[j], d0[j]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc.add<HAS_D>(y1[j], r1[j], d1[j]);
+    }
+    if (i < nvec) {
+        const f32x4 y0 = load_y4<Y_BF16>(yv, i);
+        const f32x4 r0 = r4[i];
+        f32x4 d0 = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (HAS_D) d0 = d4[i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc.add<HAS_D>(y0[j], r0[j], d0[j]);
     }
     // tail elements (n % 4), one thread each
     const int64_t t = (nvec << 2) + tid;
@@ -112,30 +126,25 @@ metric_partial(const void* __restrict__ yv, const float* __restrict__ r, const f
         else y = static_cast<const float*>(yv)[t];
         acc.add<HAS_D>(y, r[t], HAS_D ? d[t] : 0.f);
     }
-    store_partial(acc, partial + (int64_t)blockIdx.x * 16);
+    store_partial(acc, partial, (int)gridDim.x);
 }
 
-__global__ void __launch_bounds__(kThreads)
+// One workgroup of 16 wavefronts: wavefront f folds field f over the workgroup partials.  Lane l takes blocks
+// l, l+64, ... in ascending order, then the 64 lane values are folded by the fixed shuffle tree: the order of
+// additions depends on nblocks only, so results are reproducible run to run.
+__global__ void __launch_bounds__(1024)
 metric_finalize(const double* __restrict__ partial, int nblocks, double* __restrict__ out)
 {
-    // thread i < 16 folds field i over the workgroups in ascending order (fixed order => reproducible);
-    // the other threads of the workgroup idle: nblocks <= 2048 doubles per field.
-    __shared__ double s[16][kThreads / 16];
-    const int field = threadIdx.x & 15, part = threadIdx.x >> 4;   // 16 fields x 16 strided parts
+    const int field = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
     const bool is_max = (field == 4 || field == 5 || field == 7 || field == 10);
+    const double* p = partial + (int64_t)field * nblocks;
     double r = 0.0;
-    for (int b = part; b < nblocks; b += kThreads / 16) {
-        const double v = partial[(int64_t)b * 16 + field];
+    for (int b = lane; b < nblocks; b += kWave) {
+        const double v = p[b];
         r = is_max ? fmax(r, v) : r + v;
     }
-    s[field][part] = r;
-    __syncthreads();
-    if (threadIdx.x < 16) {
-        double t = s[threadIdx.x][0];
-        const bool mx = (threadIdx.x == 4 || threadIdx.x == 5 || threadIdx.x == 7 || threadIdx.x == 10);
-        for (int k = 1; k < kThreads / 16; ++k) t = mx ? fmax(t, s[threadIdx.x][k]) : t + s[threadIdx.x][k];
-        out[threadIdx.x] = t;
-    }
+    r = is_max ? wave_max_f64(r) : wave_sum_f64(r);
+    if (lane == 0) out[field] = r;
 }
 
 int plan_blocks(int64_t n)
@@ -179,6 +188,6 @@ extern "C" qmm_status qmm_metric(const void* y, qmm_dtype y_dtype, const float* 
     else if (hd) metric_partial<false, true><<<nb, kThreads, 0, s>>>(y, y_ref, denom, n, partial);
     else metric_partial<false, false><<<nb, kThreads, 0, s>>>(y, y_ref, denom, n, partial);
     if (hipGetLastError() != hipSuccess) return QMM_ERR_LAUNCH;
-    metric_finalize<<<1, kThreads, 0, s>>>(partial, nb, out16);
+    metric_finalize<<<1, 1024, 0, s>>>(partial, nb, out16);
     return launch_status();
 }
