@@ -34,6 +34,8 @@ def main():
     ap.add_argument("--workload", default="bert_large_fwd", choices=["bert_large_fwd", "bert_base_fwd"])
     ap.add_argument("--format", default="e4m3", choices=["e4m3", "e5m2", "int8"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run ten plain device copies of 256 MiB (to scale the FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -45,6 +47,14 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n = 256 << 20
+        src = torch.ones(n, dtype=torch.uint8, device=dev); dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read_per_copy": n, "bytes_written_per_copy": n, "copies": 10}}))
+        return
     fmt = qmm.FORMATS[args.format]
     cfg_no, dims = (4, W.BERT_LARGE) if args.workload == "bert_large_fwd" else (2, W.BERT_BASE)
     ops = W.bert_forward_ops(**dims)
