@@ -73,11 +73,15 @@ QMM_DEV void dma16(const uint8_t* gptr, uint8_t* lds_unit)
     __builtin_amdgcn_global_load_lds((gptr_t)gptr, (lptr_t)lds_unit, 16, 0, 0);
 }
 
-template <int KIND, int FA, int FB, int TM, int TG>
+// FUSE: bit 0 / bit 1 = the A / B operand arrives as bfloat16 values and is quantized (RTNE, with its step sizes)
+// while it is staged into LDS; otherwise it arrives as 8-bit codes and is copied by LDS-DMA.
+template <int KIND, int FA, int FB, int TM, int TG, int FUSE>
 __global__ void __launch_bounds__(kThreads, 1)
 gemm_kernel(GemmArgs g)
 {
     constexpr bool F8 = (KIND == KIND_F8);
+    constexpr bool FUSE_A = (FUSE & 1) != 0, FUSE_B = (FUSE & 2) != 0;
+    static_assert(FUSE == 0 || KIND != KIND_BF16, "only 8-bit operands are quantized on load");
     constexpr int BM = 2 * 32 * TM;            // workgroup tile rows
     constexpr int BN = 2 * 64 * TG;            // workgroup tile columns
     constexpr int WM = 32 * TM, WN = 64 * TG;  // wavefront tile
@@ -114,16 +118,17 @@ gemm_kernel(GemmArgs g)
     const int64_t tile_n = (t - grp * in_group) / gsz;
     const int64_t m0 = tile_m * BM, n0 = tile_n * BN;
 
-    const uint8_t* A = g.a + bidx * g.M * g.rowbytes;
-    const uint8_t* B = g.b + bidx * g.N * g.rowbytes;
+    constexpr int A_ES = FUSE_A ? 2 : 1, B_ES = FUSE_B ? 2 : 1;   // source bytes per K byte of codes
+    const uint8_t* A = g.a + bidx * g.M * g.rowbytes * A_ES;
+    const uint8_t* B = g.b + bidx * g.N * g.rowbytes * B_ES;
 
     // ---- DMA sources.  Unit u = LDS rows 8u..8u+7; lane l fills row 8u + l/8, chunk position l%8, i.e. fetches
     //      logical chunk (l%8) ^ ((row>>1)&7) of the global row parked there.  LDS row p of the B region holds
     //      output column  WN*(p/WN) + TILES_N*(p%R) + (p/R)%TILES_N : MFMA block t, lane j  <->  column TILES_N*j + t,
     //      so that in the accumulators a lane owns TILES_N consecutive columns of a row.
     //      Sources are kept as 32-bit byte offsets from the tile's first A / B row.
-    const uint8_t* a_tile = A + m0 * g.rowbytes;
-    const uint8_t* b_tile = B + n0 * g.rowbytes;
+    const uint8_t* a_tile = A + m0 * g.rowbytes * A_ES;
+    const uint8_t* b_tile = B + n0 * g.rowbytes * B_ES;
     uint32_t a_src[A_PER_WAVE], b_src[B_PER_WAVE];
     const int lane_chunk_base = lane & 7;
 #pragma unroll
@@ -132,7 +137,7 @@ gemm_kernel(GemmArgs g)
         const int c = lane_chunk_base ^ ((p >> 1) & 7);
         int64_t row = p;
         row = m0 + row < g.M ? row : g.M - 1 - m0;
-        a_src[i] = (uint32_t)(row * g.rowbytes + c * 16);
+        a_src[i] = (uint32_t)((row * g.rowbytes + c * 16) * A_ES);
     }
 #pragma unroll
     for (int i = 0; i < B_PER_WAVE; ++i) {
@@ -140,7 +145,7 @@ gemm_kernel(GemmArgs g)
         const int c = lane_chunk_base ^ ((p >> 1) & 7);
         int64_t row = WN * (p / WN) + TILES_N * (p % R) + (p / R) % TILES_N;
         row = n0 + row < g.N ? row : g.N - 1 - n0;
-        b_src[i] = (uint32_t)(row * g.rowbytes + c * 16);
+        b_src[i] = (uint32_t)((row * g.rowbytes + c * 16) * B_ES);
     }
 
     auto issue_loads = [&](int64_t k0, int stage) {
@@ -149,23 +154,100 @@ gemm_kernel(GemmArgs g)
         const uint8_t* ak = a_tile + k0;
         const uint8_t* bk = b_tile + k0;
         if (k0 + kSlabBytes <= g.rowbytes) {
+            if constexpr (!FUSE_A) {
 #pragma unroll
-            for (int i = 0; i < A_PER_WAVE; ++i) dma16(ak + a_src[i], sa + (wave * A_PER_WAVE + i) * 1024);
+                for (int i = 0; i < A_PER_WAVE; ++i) dma16(ak + a_src[i], sa + (wave * A_PER_WAVE + i) * 1024);
+            }
+            if constexpr (!FUSE_B) {
 #pragma unroll
-            for (int i = 0; i < B_PER_WAVE; ++i) dma16(bk + b_src[i], sb + (wave * B_PER_WAVE + i) * 1024);
+                for (int i = 0; i < B_PER_WAVE; ++i) dma16(bk + b_src[i], sb + (wave * B_PER_WAVE + i) * 1024);
+            }
         } else {   // last, partial slab: chunks past the end of the row read zeros
             const uint8_t* zero = reinterpret_cast<const uint8_t*>(g_zero16);
+            if constexpr (!FUSE_A) {
 #pragma unroll
-            for (int i = 0; i < A_PER_WAVE; ++i) {
-                const int p = (wave * A_PER_WAVE + i) * 8 + (lane >> 3);
-                const int c = lane_chunk_base ^ ((p >> 1) & 7);
-                dma16(k0 + c * 16 < g.rowbytes ? ak + a_src[i] : zero, sa + (wave * A_PER_WAVE + i) * 1024);
+                for (int i = 0; i < A_PER_WAVE; ++i) {
+                    const int p = (wave * A_PER_WAVE + i) * 8 + (lane >> 3);
+                    const int c = lane_chunk_base ^ ((p >> 1) & 7);
+                    dma16(k0 + c * 16 < g.rowbytes ? ak + a_src[i] : zero, sa + (wave * A_PER_WAVE + i) * 1024);
+                }
             }
+            if constexpr (!FUSE_B) {
 #pragma unroll
-            for (int i = 0; i < B_PER_WAVE; ++i) {
-                const int p = (wave * B_PER_WAVE + i) * 8 + (lane >> 3);
-                const int c = lane_chunk_base ^ ((p >> 1) & 7);
-                dma16(k0 + c * 16 < g.rowbytes ? bk + b_src[i] : zero, sb + (wave * B_PER_WAVE + i) * 1024);
+                for (int i = 0; i < B_PER_WAVE; ++i) {
+                    const int p = (wave * B_PER_WAVE + i) * 8 + (lane >> 3);
+                    const int c = lane_chunk_base ^ ((p >> 1) & 7);
+                    dma16(k0 + c * 16 < g.rowbytes ? bk + b_src[i] : zero, sb + (wave * B_PER_WAVE + i) * 1024);
+                }
+            }
+        }
+    };
+
+    // ---- quantize-on-load.  The fused units of this wavefront (first A's, then B's) are filled through registers:
+    // 32 bytes of bfloat16 per lane and unit are loaded, multiplied by 1/delta of the lane's row, encoded (RTNE; the
+    // same arithmetic as qmm_quantize, so the codes are identical) and written to the place in LDS where the DMA
+    // would have put the codes.  Units are handled in batches, one batch per MFMA block: the loads of a batch are
+    // issued one block before its codes are needed, so their latency sits behind matrix work.
+    constexpr int UNITS_F = (FUSE_A ? A_PER_WAVE : 0) + (FUSE_B ? B_PER_WAVE : 0);
+    constexpr int BATCH = UNITS_F == 0 ? 1 : (UNITS_F + BLOCKS_M - 1) / BLOCKS_M;     // units per batch
+    constexpr int NBATCH = UNITS_F == 0 ? 0 : (UNITS_F + BATCH - 1) / BATCH;          // <= BLOCKS_M
+    float f_rho[UNITS_F > 0 ? UNITS_F : 1];
+    u32x4 f_raw[BATCH][2];
+    if constexpr (UNITS_F > 0) {
+#pragma unroll
+        for (int f = 0; f < UNITS_F; ++f) {
+            const bool is_a = FUSE_A && f < A_PER_WAVE;
+            const int i = is_a ? f : f - (FUSE_A ? A_PER_WAVE : 0);
+            const int p = (wave * (is_a ? A_PER_WAVE : B_PER_WAVE) + i) * 8 + (lane >> 3);
+            float d;
+            if (is_a) {
+                int64_t row = m0 + p; row = row < g.M ? row : g.M - 1;
+                d = g.da[(bidx % g.da_groups) * (g.da_per_channel ? g.M : 1) + (g.da_per_channel ? row : 0)];
+            } else {
+                int64_t row = n0 + WN * (p / WN) + TILES_N * (p % R) + (p / R) % TILES_N; row = row < g.N ? row : g.N - 1;
+                d = g.db[(bidx % g.db_groups) * (g.db_per_channel ? g.N : 1) + (g.db_per_channel ? row : 0)];
+            }
+            f_rho[f] = 1.0f / d;
+        }
+    }
+    auto fused_load = [&](int batch, int64_t k0) {
+        if constexpr (UNITS_F > 0) {
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int f = batch * BATCH + u;
+                if (f < UNITS_F) {
+                    const bool is_a = FUSE_A && f < A_PER_WAVE;
+                    const int i = is_a ? f : f - (FUSE_A ? A_PER_WAVE : 0);
+                    const int p = (wave * (is_a ? A_PER_WAVE : B_PER_WAVE) + i) * 8 + (lane >> 3);
+                    const int c = lane_chunk_base ^ ((p >> 1) & 7);
+                    const uint8_t* src = (is_a ? a_tile + a_src[i] : b_tile + b_src[i]) + k0 * 2;
+                    if (k0 + c * 16 < g.rowbytes) {
+                        f_raw[u][0] = reinterpret_cast<const u32x4*>(src)[0];
+                        f_raw[u][1] = reinterpret_cast<const u32x4*>(src)[1];
+                    } else {
+                        f_raw[u][0] = u32x4{0u, 0u, 0u, 0u};
+                        f_raw[u][1] = u32x4{0u, 0u, 0u, 0u};
+                    }
+                }
+            }
+        }
+    };
+    auto fused_store = [&](int batch, int stage) {
+        if constexpr (UNITS_F > 0) {
+            uint8_t* sa = lds + stage * STAGE_BYTES;
+            uint8_t* sb = sa + BM * kSlabBytes;
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int f = batch * BATCH + u;
+                if (f < UNITS_F) {
+                    const bool is_a = FUSE_A && f < A_PER_WAVE;
+                    const int i = is_a ? f : f - (FUSE_A ? A_PER_WAVE : 0);
+                    uint8_t* dst = (is_a ? sa + (wave * A_PER_WAVE + i) * 1024 : sb + (wave * B_PER_WAVE + i) * 1024) + lane * 16;
+                    u32x4 codes;
+                    if (is_a) codes = encode16_bf16_rtne<FA>(f_raw[u][0], f_raw[u][1], f_rho[f]);
+                    else codes = encode16_bf16_rtne<FB>(f_raw[u][0], f_raw[u][1], f_rho[f]);
+                    *reinterpret_cast<u32x4*>(dst) = codes;
+                }
             }
         }
     };
@@ -223,9 +305,13 @@ gemm_kernel(GemmArgs g)
 
     const int64_t nk = (g.rowbytes + kSlabBytes - 1) / kSlabBytes;
     issue_loads(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (UNITS_F > 0) {
+#pragma unroll
+        for (int bt = 0; bt < NBATCH; ++bt) { fused_load(bt, 0); fused_store(bt, 0); }
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __syncthreads();
-    if (nk > 1) issue_loads(kSlabBytes, 1);
+    if (nk > 1) { issue_loads(kSlabBytes, 1); fused_load(0, kSlabBytes); }
     {
         const uint8_t* sb = lds + b_off;
 #pragma unroll
@@ -244,6 +330,13 @@ gemm_kernel(GemmArgs g)
         const int stage = (int)(kt & 1);
 #pragma unroll
         for (int i = 0; i < BLOCKS_M - 1; ++i) {
+            if constexpr (UNITS_F > 0) {
+                // quantize-on-load: codes of batch i of the next slab go to LDS, batch i+1 is requested
+                if (kt + 1 < nk) {
+                    if (i < NBATCH) fused_store(i, stage ^ 1);
+                    if (i + 1 < NBATCH) fused_load(i + 1, (kt + 1) * kSlabBytes);
+                }
+            }
             // first MFMA of the block, then the request for the next block's fragments, then the rest: whatever
             // wait the compiler puts in front of the first MFMA then never covers the newest request
             mma(fa[i & 1][0], fb[0][0], acc[i][0]);
@@ -259,9 +352,10 @@ gemm_kernel(GemmArgs g)
         }
         const bool more = kt + 1 < nk;
         if (more) {
+            if constexpr (UNITS_F > 0) { if (NBATCH == BLOCKS_M) fused_store(BLOCKS_M - 1, stage ^ 1); }
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             __syncthreads();
-            if (kt + 2 < nk) issue_loads((kt + 2) * kSlabBytes, stage);
+            if (kt + 2 < nk) { issue_loads((kt + 2) * kSlabBytes, stage); fused_load(0, (kt + 2) * kSlabBytes); }
             read_a(stage ^ 1, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -373,7 +467,7 @@ gemm_kernel(GemmArgs g)
     }
 }
 
-template <int KIND, int FA, int FB, int TM, int TG>
+template <int KIND, int FA, int FB, int TM, int TG, int FUSE>
 qmm_status launch_tile(GemmArgs& g, hipStream_t s)
 {
     constexpr int BM = 2 * 32 * TM, BN = 2 * 64 * TG;
@@ -383,7 +477,7 @@ qmm_status launch_tile(GemmArgs& g, hipStream_t s)
     g.tiles_n = (int)((g.N + BN - 1) / BN);
     const int64_t total = (int64_t)g.tiles_m * g.tiles_n * g.batch;
     if (total > 0x7FFFFFFF) return QMM_ERR_UNSUPPORTED;
-    auto kern = gemm_kernel<KIND, FA, FB, TM, TG>;
+    auto kern = gemm_kernel<KIND, FA, FB, TM, TG, FUSE>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
@@ -394,13 +488,27 @@ qmm_status launch_tile(GemmArgs& g, hipStream_t s)
     return launch_status();
 }
 
-template <int KIND, int FA, int FB>
-qmm_status launch_kind(GemmArgs& g, hipStream_t s)
+template <int KIND, int FA, int FB, int FUSE>
+qmm_status launch_fuse(GemmArgs& g, hipStream_t s)
 {
     // 256 x 256 tiles when they still give every CU work, else 128 x 128.
     const int64_t big = ((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
-    if (big >= 192) return launch_tile<KIND, FA, FB, 4, 2>(g, s);
-    return launch_tile<KIND, FA, FB, 2, 1>(g, s);
+    if (big >= 192) return launch_tile<KIND, FA, FB, 4, 2, FUSE>(g, s);
+    return launch_tile<KIND, FA, FB, 2, 1, FUSE>(g, s);
+}
+
+// fuse: bit 0 = A is quantized on load, bit 1 = B is
+template <int KIND, int FA, int FB>
+qmm_status launch_kind(GemmArgs& g, hipStream_t s, int fuse)
+{
+    if constexpr (KIND == KIND_BF16) {
+        return launch_fuse<KIND, FA, FB, 0>(g, s);
+    } else {
+        if (fuse == 0) return launch_fuse<KIND, FA, FB, 0>(g, s);
+        if (fuse == 1) return launch_fuse<KIND, FA, FB, 1>(g, s);
+        if (fuse == 2) return launch_fuse<KIND, FA, FB, 2>(g, s);
+        return launch_fuse<KIND, FA, FB, 3>(g, s);
+    }
 }
 
 bool is8(int f) { return f == QMM_FMT_INT8 || f == QMM_FMT_E4M3 || f == QMM_FMT_E5M2; }
@@ -440,7 +548,7 @@ extern "C" qmm_status qmm_gemm(const qmm_operand* a, const qmm_operand* b, int64
     const bool bf = a->format == QMM_FMT_BF16;
     if (bf != (b->format == QMM_FMT_BF16)) return QMM_ERR_UNSUPPORTED;
     if (!bf && ((a->format == QMM_FMT_INT8) != (b->format == QMM_FMT_INT8))) return QMM_ERR_UNSUPPORTED;
-    if (!bf && (!a->is_codes || !b->is_codes)) return QMM_ERR_UNSUPPORTED;   // quantize-on-load: not in this build yet
+    const int fuse = bf ? 0 : ((a->is_codes ? 0 : 1) | (b->is_codes ? 0 : 2));
     if (!y && !acc_out) return QMM_ERR_NULL;
     if (batch * M * N == 0) return QMM_OK;
     if (!bf && (!a->delta || !b->delta)) return QMM_ERR_NULL;
@@ -459,10 +567,10 @@ extern "C" qmm_status qmm_gemm(const qmm_operand* a, const qmm_operand* b, int64
     g.y = y; g.y_bf16 = y_dtype == QMM_DT_BF16; g.acc_out = acc_out;
     hipStream_t s = as_stream(stream);
 
-    if (bf) return launch_kind<KIND_BF16, QMM_FMT_BF16, QMM_FMT_BF16>(g, s);
-    if (a->format == QMM_FMT_INT8) return launch_kind<KIND_I8, QMM_FMT_INT8, QMM_FMT_INT8>(g, s);
-    if (a->format == QMM_FMT_E4M3 && b->format == QMM_FMT_E4M3) return launch_kind<KIND_F8, QMM_FMT_E4M3, QMM_FMT_E4M3>(g, s);
-    if (a->format == QMM_FMT_E4M3) return launch_kind<KIND_F8, QMM_FMT_E4M3, QMM_FMT_E5M2>(g, s);
-    if (b->format == QMM_FMT_E4M3) return launch_kind<KIND_F8, QMM_FMT_E5M2, QMM_FMT_E4M3>(g, s);
-    return launch_kind<KIND_F8, QMM_FMT_E5M2, QMM_FMT_E5M2>(g, s);
+    if (bf) return launch_kind<KIND_BF16, QMM_FMT_BF16, QMM_FMT_BF16>(g, s, 0);
+    if (a->format == QMM_FMT_INT8) return launch_kind<KIND_I8, QMM_FMT_INT8, QMM_FMT_INT8>(g, s, fuse);
+    if (a->format == QMM_FMT_E4M3 && b->format == QMM_FMT_E4M3) return launch_kind<KIND_F8, QMM_FMT_E4M3, QMM_FMT_E4M3>(g, s, fuse);
+    if (a->format == QMM_FMT_E4M3) return launch_kind<KIND_F8, QMM_FMT_E4M3, QMM_FMT_E5M2>(g, s, fuse);
+    if (b->format == QMM_FMT_E4M3) return launch_kind<KIND_F8, QMM_FMT_E5M2, QMM_FMT_E4M3>(g, s, fuse);
+    return launch_kind<KIND_F8, QMM_FMT_E5M2, QMM_FMT_E5M2>(g, s, fuse);
 }

@@ -11,7 +11,7 @@ namespace qmm {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxBlocks = 2048;
+constexpr int kMaxBlocks = 1024;   // 4 workgroups per CU; also 16 partials per lane in the final fold
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
@@ -138,11 +138,16 @@ metric_finalize(const double* __restrict__ partial, int nblocks, double* __restr
     const int field = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
     const bool is_max = (field == 4 || field == 5 || field == 7 || field == 10);
     const double* p = partial + (int64_t)field * nblocks;
-    double r = 0.0;
-    for (int b = lane; b < nblocks; b += kWave) {
-        const double v = p[b];
-        r = is_max ? fmax(r, v) : r + v;
+    // all of a lane's partials are requested before any is used (kMaxBlocks / 64 = 16 independent loads)
+    double v[kMaxBlocks / kWave];
+#pragma unroll
+    for (int k = 0; k < kMaxBlocks / kWave; ++k) {
+        const int b = lane + k * kWave;
+        v[k] = b < nblocks ? p[b] : 0.0;
     }
+    double r = 0.0;
+#pragma unroll
+    for (int k = 0; k < kMaxBlocks / kWave; ++k) r = is_max ? fmax(r, v[k]) : r + v[k];
     r = is_max ? wave_max_f64(r) : wave_sum_f64(r);
     if (lane == 0) out[field] = r;
 }

@@ -43,22 +43,25 @@ quantize_rows_bf16x16(QArgs a)
                                                       r * a.row_stride + cv * 16);
     const u32x4 w0 = src[0], w1 = src[1];
     const int64_t p0 = (b * a.rows + r) * a.cols + cv * 16;
-    SrStream sr(a.seed);
     u32x4 out;
+    if constexpr (MODE == QMM_ROUND_RTNE) {
+        out = encode16_bf16_rtne<FMT>(w0, w1, rho);
+    } else {
+        SrStream sr(a.seed);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        uint32_t packed = 0;
+        for (int q = 0; q < 4; ++q) {
+            uint32_t packed = 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int e = q * 4 + j;
-            const uint32_t word = e < 8 ? w0[e >> 1] : w1[(e - 8) >> 1];
-            const float xv = (e & 1) ? __uint_as_float(word & 0xFFFF0000u) : __uint_as_float(word << 16);
-            const float t = xv * rho;
-            uint32_t u24 = 0;
-            if constexpr (MODE == QMM_ROUND_STOCHASTIC) u24 = sr.bits((uint64_t)(p0 + e) + a.offset);
-            packed |= encode<FMT, MODE>(t, u24) << (8 * j);
+            for (int j = 0; j < 4; ++j) {
+                const int e = q * 4 + j;
+                const uint32_t word = e < 8 ? w0[e >> 1] : w1[(e - 8) >> 1];
+                const float xv = (e & 1) ? __uint_as_float(word & 0xFFFF0000u) : __uint_as_float(word << 16);
+                const float t = xv * rho;
+                const uint32_t u24 = sr.bits((uint64_t)(p0 + e) + a.offset);
+                packed |= encode<FMT, MODE>(t, u24) << (8 * j);
+            }
+            out[q] = packed;
         }
-        out[q] = packed;
     }
     *reinterpret_cast<u32x4*>(a.codes + p0) = out;
 }

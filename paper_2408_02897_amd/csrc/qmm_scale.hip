@@ -11,7 +11,7 @@ namespace qmm {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxFlatBlocks = 2048;   // 8 workgroups per CU on 256 CUs
+constexpr int kMaxFlatBlocks = 1024;   // 4 workgroups per CU on 256 CUs; 4 partials per thread in the fold
 constexpr int kColSlabRows = 256;      // rows folded by one workgroup in the column-group kernel
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
@@ -150,8 +150,19 @@ finalize_single(const uint32_t* __restrict__ partial, int64_t batch, int64_t P, 
 {
     const int64_t g = blockIdx.x;
     uint32_t m = 0;
-    for (int64_t b = g; b < batch; b += G)
-        for (int64_t p = threadIdx.x; p < P; p += kThreads) m = max(m, partial[b * P + p]);
+    if (batch <= G && P <= 4 * kThreads) {
+        // one matrix per group and few partials: request them all before folding
+        uint32_t v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int64_t p = threadIdx.x + k * kThreads;
+            v[k] = (g < batch && p < P) ? partial[g * P + p] : 0u;
+        }
+        m = max(max(v[0], v[1]), max(v[2], v[3]));
+    } else {
+        for (int64_t b = g; b < batch; b += G)
+            for (int64_t p = threadIdx.x; p < P; p += kThreads) m = max(m, partial[b * P + p]);
+    }
     m = block_max_u32(m);
     if (threadIdx.x == 0) delta[g] = delta_from_absmax_bits(m, qmax);
 }

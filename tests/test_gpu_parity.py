@@ -260,6 +260,44 @@ def test_gemm_per_head_scales_and_batch_groups():
     assert np.all(np.abs(acc.cpu().numpy() - want_acc) <= hw_fp8_bound(a, O.E4M3, b, O.E4M3, sabs))
 
 
+FUSED_SHAPES = [(1, 256, 768, 768), (1, 200, 136, 400), (3, 130, 80, 64), (1, 520, 528, 1040), (2, 257, 512, 272),
+                (1, 64, 1000, 48), (1, 1024, 1024, 256)]
+
+
+@pytest.mark.parametrize("shape", FUSED_SHAPES)
+@pytest.mark.parametrize("fa,fb", [(qmm.INT8, qmm.INT8), (qmm.E4M3, qmm.E4M3), (qmm.E5M2, qmm.E4M3), (qmm.E4M3, qmm.E5M2)])
+@pytest.mark.parametrize("per_channel", [False, True])
+def test_gemm_quantize_on_load_matches_separate_quantize(shape, fa, fb, per_channel):
+    """An operand handed over as bfloat16 values with its step sizes is encoded while it is staged: the codes, and so
+    the accumulators and outputs, are those of qmm_quantize followed by qmm_gemm on codes (bit for bit), and the codes
+    are the oracle's."""
+    bt, M, N, K = shape
+    x = W.student_t((bt, M, K), 4, 21); w = W.normal((bt, N, K), 0.02, 22)
+    xd, wd = x.to(DEV).contiguous(), w.to(DEV).contiguous()
+    groups = bt if bt > 1 else 1
+    dx = qmm.scale(xd, 1, fa, per_channel, groups); dw = qmm.scale(wd, 1, fb, per_channel, groups)
+    # planted after the step sizes were taken: values far beyond the range saturate; NaN -> 0 in INT8 (an FP8 NaN
+    # would only flood its output row)
+    x.view(-1)[5] = 1e30; x.view(-1)[K + 3] = -1e30
+    if fa == qmm.INT8:
+        x.view(-1)[7] = float("nan")
+    xd = x.to(DEV).contiguous()
+    cx = qmm.quantize(xd, 1, fa, dx, per_channel, groups); cw = qmm.quantize(wd, 1, fb, dw, per_channel, groups)
+    assert np.array_equal(cx.cpu().numpy(), O.quantize(np32(x), 1, fa, dx.cpu().numpy(), per_channel, groups))
+    assert np.array_equal(cw.cpu().numpy(), O.quantize(np32(w), 1, fb, dw.cpu().numpy(), per_channel, groups))
+    oc_x = qmm.operand(cx, fa, dx, per_channel, groups); oc_w = qmm.operand(cw, fb, dw, per_channel, groups)
+    ov_x = qmm.operand(xd, fa, dx, per_channel, groups, is_codes=False)
+    ov_w = qmm.operand(wd, fb, dw, per_channel, groups, is_codes=False)
+    y0, acc0 = qmm.gemm((cx, oc_x), (cw, oc_w), torch.float32, want_acc=True)
+    for (a, b) in [((xd, ov_x), (cw, oc_w)), ((cx, oc_x), (wd, ov_w)), ((xd, ov_x), (wd, ov_w))]:
+        y1, acc1 = qmm.gemm(a, b, torch.float32, want_acc=True)
+        assert torch.equal(acc1.view(torch.int32), acc0.view(torch.int32))
+        assert torch.equal(y1.view(torch.int32), y0.view(torch.int32))
+    yb0 = qmm.gemm((cx, oc_x), (cw, oc_w), torch.bfloat16)
+    yb1 = qmm.gemm((xd, ov_x), (wd, ov_w), torch.bfloat16)
+    assert torch.equal(yb0.view(torch.int16), yb1.view(torch.int16))
+
+
 def test_reference_gemm():
     for (bt, M, N, K) in [(1, 256, 768, 768), (2, 100, 72, 200), (1, 130, 258, 520)]:
         x = W.normal((bt, M, K), 1.0, 5); w = W.normal((bt, N, K), 0.02, 6)
