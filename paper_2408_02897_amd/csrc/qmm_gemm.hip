@@ -31,6 +31,7 @@
 #include <type_traits>
 
 #include "qmm_device.h"
+#include <cstdlib>
 
 namespace qmm {
 namespace {
@@ -47,10 +48,10 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 enum Kind { KIND_I8 = 0, KIND_F8 = 1, KIND_BF16 = 2 };
 
 constexpr int kThreads = 256;
+constexpr int kASlots = 3, kBSlots = 2;   // LDS ring depths of the two operands
 constexpr int kSlabBytes = 128;      // K bytes per row per pipeline step = one LDS row
 constexpr int kNumXcd = 8;
 
-__device__ __attribute__((aligned(16))) const uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};
 
 struct GemmArgs {
     const uint8_t* a;        // [batch][M][rowbytes]
@@ -73,6 +74,29 @@ QMM_DEV void dma16(const uint8_t* gptr, uint8_t* lds_unit)
     __builtin_amdgcn_global_load_lds((gptr_t)gptr, (lptr_t)lds_unit, 16, 0, 0);
 }
 
+// The same copy with the source given as a wavefront-uniform base plus a 32-bit byte offset per lane, and the LDS
+// unit as a wavefront-uniform LDS address: one scalar move and the copy instruction, no vector address arithmetic.
+// Issued this way a copy costs the wavefront about ten cycles; with a 64-bit vector address and the LDS address
+// taken through a lane read it costs several times that, and sixteen of them in a row held up the matrix
+// instructions for longer than a whole A block takes.
+QMM_DEV void dma16_uniform(const uint8_t* base, uint32_t lane_offset, uint32_t lds_unit_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_unit_addr), "v"(lane_offset), "s"(base) : "memory", "m0");
+}
+
+// s_waitcnt with a compile-time count of vector-memory operations that may remain outstanding
+template <int N> QMM_DEV void wait_vm()
+{
+    static_assert(N >= 0 && N <= 63, "vmcnt range");
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+template <int N> QMM_DEV void wait_vm_lgkm()
+{
+    static_assert(N >= 0 && N <= 63, "vmcnt range");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(N) : "memory");
+}
+
 // FUSE: bit 0 / bit 1 = the A / B operand arrives as bfloat16 values and is quantized (RTNE, with its step sizes)
 // while it is staged into LDS; otherwise it arrives as 8-bit codes and is copied by LDS-DMA.
 template <int KIND, int FA, int FB, int TM, int TG, int FUSE>
@@ -89,13 +113,16 @@ gemm_kernel(GemmArgs g)
     constexpr int BLOCKS_M = WM / R;           // A blocks per wavefront
     constexpr int TILES_N = WN / R;            // B blocks per wavefront
     constexpr int KS = F8 ? 1 : 4;             // MFMA K slices per 128-byte slab
-    constexpr int STAGE_BYTES = (BM + BN) * kSlabBytes;
+    constexpr int A_SLOT = BM * kSlabBytes, B_SLOT = BN * kSlabBytes;   // one K slab of A / of B in LDS
+    constexpr int B_BASE = kASlots * A_SLOT;                            // LDS: kASlots A slabs, then kBSlots B slabs
     constexpr int A_UNITS = BM / 8, B_UNITS = BN / 8;          // DMA units of 8 LDS rows
     constexpr int A_PER_WAVE = A_UNITS / 4, B_PER_WAVE = B_UNITS / 4;
     static_assert(BLOCKS_M % 2 == 0, "A fragments ping-pong between two register sets");
+    static_assert(A_PER_WAVE % 2 == 0 && B_PER_WAVE % 2 == 0, "a wavefront's units start on an even LDS row pair");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: kept in a scalar register
     const int wm = wave >> 1, wn = wave & 1;
 
     // ---- workgroup id -> (batch, tile_m, tile_n), XCD-aware and grouped along m
@@ -107,15 +134,17 @@ gemm_kernel(GemmArgs g)
         const int64_t xcd = pid % kNumXcd, loc = pid / kNumXcd;
         pid = (tall == 0 || xcd < tall) ? xcd * per + loc : tall * per + (xcd - tall) * (per - 1) + loc;
     }
-    const int64_t bidx = pid / tiles_per_batch;
+    // the divisions run on the vector unit; their results are the same in every lane and are moved to scalar
+    // registers, so that everything derived from them (tile base addresses above all) is scalar as well
+    const int64_t bidx = __builtin_amdgcn_readfirstlane((int)(pid / tiles_per_batch));
     const int64_t t = pid - bidx * tiles_per_batch;
     constexpr int GROUP_M = 8;
     const int64_t in_group = (int64_t)GROUP_M * g.tiles_n;
     const int64_t grp = t / in_group;
     const int64_t first_m = grp * GROUP_M;
     const int64_t gsz = min((int64_t)GROUP_M, g.tiles_m - first_m);
-    const int64_t tile_m = first_m + (t - grp * in_group) % gsz;
-    const int64_t tile_n = (t - grp * in_group) / gsz;
+    const int64_t tile_m = __builtin_amdgcn_readfirstlane((int)(first_m + (t - grp * in_group) % gsz));
+    const int64_t tile_n = __builtin_amdgcn_readfirstlane((int)((t - grp * in_group) / gsz));
     const int64_t m0 = tile_m * BM, n0 = tile_n * BN;
 
     constexpr int A_ES = FUSE_A ? 2 : 1, B_ES = FUSE_B ? 2 : 1;   // source bytes per K byte of codes
@@ -148,39 +177,32 @@ gemm_kernel(GemmArgs g)
         b_src[i] = (uint32_t)((row * g.rowbytes + c * 16) * B_ES);
     }
 
-    auto issue_loads = [&](int64_t k0, int stage) {
-        uint8_t* sa = lds + stage * STAGE_BYTES;
-        uint8_t* sb = sa + BM * kSlabBytes;
-        const uint8_t* ak = a_tile + k0;
-        const uint8_t* bk = b_tile + k0;
-        if (k0 + kSlabBytes <= g.rowbytes) {
-            if constexpr (!FUSE_A) {
-#pragma unroll
-                for (int i = 0; i < A_PER_WAVE; ++i) dma16(ak + a_src[i], sa + (wave * A_PER_WAVE + i) * 1024);
-            }
-            if constexpr (!FUSE_B) {
-#pragma unroll
-                for (int i = 0; i < B_PER_WAVE; ++i) dma16(bk + b_src[i], sb + (wave * B_PER_WAVE + i) * 1024);
-            }
-        } else {   // last, partial slab: chunks past the end of the row read zeros
-            const uint8_t* zero = reinterpret_cast<const uint8_t*>(g_zero16);
-            if constexpr (!FUSE_A) {
-#pragma unroll
-                for (int i = 0; i < A_PER_WAVE; ++i) {
-                    const int p = (wave * A_PER_WAVE + i) * 8 + (lane >> 3);
-                    const int c = lane_chunk_base ^ ((p >> 1) & 7);
-                    dma16(k0 + c * 16 < g.rowbytes ? ak + a_src[i] : zero, sa + (wave * A_PER_WAVE + i) * 1024);
-                }
-            }
-            if constexpr (!FUSE_B) {
-#pragma unroll
-                for (int i = 0; i < B_PER_WAVE; ++i) {
-                    const int p = (wave * B_PER_WAVE + i) * 8 + (lane >> 3);
-                    const int c = lane_chunk_base ^ ((p >> 1) & 7);
-                    dma16(k0 + c * 16 < g.rowbytes ? bk + b_src[i] : zero, sb + (wave * B_PER_WAVE + i) * 1024);
-                }
-            }
+    // Copy number i of this wavefront for the A (B) slab at byte k0 into ring slot `slot`.
+    typedef __attribute__((address_space(3))) uint8_t* lds_ptr_t;
+    const uint32_t lds_a_units = (uint32_t)(uintptr_t)(lds_ptr_t)(lds + wave * A_PER_WAVE * 1024);
+    const uint32_t lds_b_units = (uint32_t)(uintptr_t)(lds_ptr_t)(lds + B_BASE + wave * B_PER_WAVE * 1024);
+    // A partial last slab (K not a multiple of the slab width): lanes whose 16-byte chunk lies past the end of the
+    // row write zeros to their place in LDS, the others copy as usual with those lanes masked off.
+    const int rowbytes = (int)g.rowbytes;      // at most 2^22, checked on the host
+    auto copy_unit = [&](const uint8_t* base, uint32_t lane_offset, uint32_t lds_unit_addr, uint8_t* lds_unit, int chunk,
+                         int k0) {
+        if (k0 + kSlabBytes <= rowbytes) {
+            dma16_uniform(base + k0, lane_offset, lds_unit_addr);
+        } else if (k0 + chunk * 16 < rowbytes) {
+            dma16_uniform(base + k0, lane_offset, lds_unit_addr);
+        } else {
+            *reinterpret_cast<u32x4*>(lds_unit + lane * 16) = u32x4{0u, 0u, 0u, 0u};
         }
+    };
+    auto copy_a = [&](int i, int k0, int slot) {
+        const int chunk = lane_chunk_base ^ ((i * 4 + (lane >> 4)) & 7);
+        copy_unit(a_tile, a_src[i], lds_a_units + slot * A_SLOT + i * 1024,
+                  lds + slot * A_SLOT + (wave * A_PER_WAVE + i) * 1024, chunk, k0);
+    };
+    auto copy_b = [&](int i, int k0, int slot) {
+        const int chunk = lane_chunk_base ^ ((i * 4 + (lane >> 4)) & 7);
+        copy_unit(b_tile, b_src[i], lds_b_units + slot * B_SLOT + i * 1024,
+                  lds + B_BASE + slot * B_SLOT + (wave * B_PER_WAVE + i) * 1024, chunk, k0);
     };
 
     // ---- quantize-on-load.  The fused units of this wavefront (first A's, then B's) are filled through registers:
@@ -232,10 +254,10 @@ gemm_kernel(GemmArgs g)
             }
         }
     };
-    auto fused_store = [&](int batch, int stage) {
+    auto fused_store = [&](int batch, int a_slot_w, int b_slot_w) {
         if constexpr (UNITS_F > 0) {
-            uint8_t* sa = lds + stage * STAGE_BYTES;
-            uint8_t* sb = sa + BM * kSlabBytes;
+            uint8_t* sa = lds + a_slot_w * A_SLOT;
+            uint8_t* sb = lds + B_BASE + b_slot_w * B_SLOT;
 #pragma unroll
             for (int u = 0; u < BATCH; ++u) {
                 const int f = batch * BATCH + u;
@@ -269,7 +291,7 @@ gemm_kernel(GemmArgs g)
     const int fkey = (frow >> 1) & 7;
     const int fsel = F8 ? (lane >> 4) : (lane >> 5);
     const int a_off = (wm * WM + frow) * kSlabBytes;
-    const int b_off = BM * kSlabBytes + (wn * WN + frow) * kSlabBytes;
+    const int b_off = B_BASE + (wn * WN + frow) * kSlabBytes;
     int coff[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) coff[s] = ((F8 ? fsel : 2 * s + fsel) ^ fkey) * 16;
@@ -283,35 +305,88 @@ gemm_kernel(GemmArgs g)
             return *reinterpret_cast<const v4i*>(row_ptr + coff[s]);
         }
     };
+    // The matrix instructions are written out with the accumulator tied ("+a": same AGPRs in and out).  Left to the
+    // compiler, some instantiations of this loop got the three-address form, which copies every accumulator
+    // block through a temporary in front of its MFMA (four moves and a pipeline wait per instruction).
+    // What the compiler no longer sees and this kernel guarantees itself: an accumulator block is next touched a
+    // whole K step later (no back-to-back dependent MFMAs), and accumulators are first read (epilogue) behind the
+    // wait states placed after the loop.
     auto mma = [&](const Frag& fa, const Frag& fb, AccT& c) {
         // first operand: A rows -> the 4-row groups held in a lane's registers; second: B rows -> lane%R
-        if constexpr (F8)
-            c = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fa, fb, c, FA == QMM_FMT_E5M2 ? 1 : 0,
-                                                                 FB == QMM_FMT_E5M2 ? 1 : 0, 0, 0, 0, 0);
-        else if constexpr (KIND == KIND_I8)
-            c = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, c, 0, 0, 0);
-        else
-            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fa), __builtin_bit_cast(v8bf, fb), c, 0, 0, 0);
+        // (device pass only: the host pass would check these register constraints against the host's)
+#if defined(__HIP_DEVICE_COMPILE__)
+        if constexpr (F8) {
+            if constexpr (FA == QMM_FMT_E5M2 && FB == QMM_FMT_E5M2)
+                asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 cbsz:1 blgp:1" : "+a"(c) : "v"(fa), "v"(fb));
+            else if constexpr (FA == QMM_FMT_E5M2)
+                asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 cbsz:1" : "+a"(c) : "v"(fa), "v"(fb));
+            else if constexpr (FB == QMM_FMT_E5M2)
+                asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 blgp:1" : "+a"(c) : "v"(fa), "v"(fb));
+            else
+                asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(c) : "v"(fa), "v"(fb));
+        } else if constexpr (KIND == KIND_I8) {
+            asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+a"(c) : "v"(fa), "v"(fb));
+        } else {
+            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(fa), "v"(fb));
+        }
+#endif
     };
 
     Frag fb[KS][TILES_N];      // B fragments of the current slab
     Frag fa[2][KS];            // A fragments of one block, ping-pong between blocks
 
-    auto read_a = [&](int stage, int i, int buf) {
-        const uint8_t* sa = lds + stage * STAGE_BYTES + a_off + i * R * kSlabBytes;
+    auto read_a = [&](int slot, int i, int buf) {
+        const uint8_t* sa = lds + slot * A_SLOT + a_off + i * R * kSlabBytes;
 #pragma unroll
         for (int s = 0; s < KS; ++s) fa[buf][s] = read_frag(sa, s);
     };
 
-    const int64_t nk = (g.rowbytes + kSlabBytes - 1) / kSlabBytes;
-    issue_loads(0, 0);
+    // ---- pipeline.  K slab s of A lives in A slot s % 3, of B in B slot s % 2; the B fragments of the current slab
+    // live in registers for the whole step, which serves as a third B stage.  Once per K step, before the last A
+    // block, the wavefronts meet (E_s): every LDS read of slab s has completed, and slabs s+1 have landed.  After
+    // E_s, A slot s%3 and B slot s%2 are free.  Copies are requested one or two at a time between matrix
+    // instructions (a burst of sixteen parks the wavefront at the memory pipeline for about 1000 cycles, with no
+    // matrix work issued meanwhile), in this order:
+    //     last block of step s   : the first half of B slab s+2
+    //     blocks 0.. of step s+1 : the second half of B slab s+2, then A slab s+3
+    // B slab s+2 has until E_(s+1) to arrive, A slab s+3 until E_(s+2).  Loads complete in order, so at E_s "at
+    // most the A copies of this step outstanding" (vmcnt) means slabs s+1 are in LDS.
+    // With quantize-on-load, a fused operand's slab s+1 is encoded into its slot during step s instead.
+    constexpr int NA = FUSE_A ? 0 : A_PER_WAVE, NB = FUSE_B ? 0 : B_PER_WAVE;
+    constexpr int NB_TAIL = NB / 2;                                 // B copies requested in a step's last block
+    constexpr int MMAS_PER_BLOCK = KS * TILES_N;
+    constexpr int N1 = (BLOCKS_M - 1) * MMAS_PER_BLOCK;             // MFMAs before E
+    constexpr int NC = (NB - NB_TAIL) + NA;                         // copies requested among them
+    static_assert(NC <= N1 && NB_TAIL <= MMAS_PER_BLOCK, "one copy per MFMA at most");
+
+    const int nk = (rowbytes + kSlabBytes - 1) / kSlabBytes;
+    // prologue: slab 0 of both operands, A slab 1, the first half of B slab 1 (what the steps before would have
+    // requested); A slab 2 and the rest of B slab 1 follow inside step 0
+    if constexpr (!FUSE_A) {
+#pragma unroll
+        for (int i = 0; i < A_PER_WAVE; ++i) copy_a(i, 0, 0);
+    }
+    if constexpr (!FUSE_B) {
+#pragma unroll
+        for (int i = 0; i < B_PER_WAVE; ++i) copy_b(i, 0, 0);
+    }
     if constexpr (UNITS_F > 0) {
 #pragma unroll
-        for (int bt = 0; bt < NBATCH; ++bt) { fused_load(bt, 0); fused_store(bt, 0); }
+        for (int bt = 0; bt < NBATCH; ++bt) { fused_load(bt, 0); fused_store(bt, 0, 0); }
     }
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    if (nk > 1) {
+        if constexpr (!FUSE_A) {
+#pragma unroll
+            for (int i = 0; i < A_PER_WAVE; ++i) copy_a(i, kSlabBytes, 1);
+        }
+#pragma unroll
+        for (int i = 0; i < NB_TAIL; ++i) copy_b(i, kSlabBytes, 1);
+        wait_vm<NA + NB_TAIL>();
+    } else {
+        wait_vm<0>();
+    }
     __syncthreads();
-    if (nk > 1) { issue_loads(kSlabBytes, 1); fused_load(0, kSlabBytes); }
+    if (nk > 1) fused_load(0, kSlabBytes);
     {
         const uint8_t* sb = lds + b_off;
 #pragma unroll
@@ -321,54 +396,86 @@ gemm_kernel(GemmArgs g)
     }
     read_a(0, 0, 0);
 
-    // One K step.  On entry fb and fa[0] hold this slab's first fragments and the DMA of the next slab is in
-    // flight.  The fragments of A block i+1 are requested before the MFMAs of block i are issued.  Before the last
-    // block the wavefronts meet: every read of this slab has completed and the next slab has landed; the last
-    // block's MFMAs then run while each B fragment register is refilled from the next slab right after its last
-    // use, so LDS latency hides behind matrix work and the B fragments need one register set only.
-    for (int64_t kt = 0; kt < nk; ++kt) {
-        const int stage = (int)(kt & 1);
+    asm volatile("s_nop 7" ::: "memory");     // accumulator initialisation -> first matrix instruction
+    __builtin_amdgcn_sched_barrier(0);
+    int a_slot = 0;                            // kt % 3
+    for (int kt = 0; kt < nk; ++kt) {
+        const int b_slot = kt & 1;
+        const int a_next = a_slot == 2 ? 0 : a_slot + 1;          // slot of A slab kt+1
+        const int a_free = a_slot == 0 ? 2 : a_slot - 1;          // slot of A slab kt+2 (slab kt-1 left it at E_(kt-1))
+        const bool more = kt + 1 < nk, more2 = kt + 2 < nk;
+        const int k1 = (kt + 1) * kSlabBytes, k2 = (kt + 2) * kSlabBytes;
+        // copy number c of the blocks before E: the rest of B slab kt+1, then A slab kt+2
+        auto copy_before_e = [&](int c) {
+            if (c < NB - NB_TAIL) { if (more) copy_b(NB_TAIL + c, k1, b_slot ^ 1); }
+            else { if (more2) copy_a(c - (NB - NB_TAIL), k2, a_free); }
+        };
 #pragma unroll
         for (int i = 0; i < BLOCKS_M - 1; ++i) {
             if constexpr (UNITS_F > 0) {
                 // quantize-on-load: codes of batch i of the next slab go to LDS, batch i+1 is requested
-                if (kt + 1 < nk) {
-                    if (i < NBATCH) fused_store(i, stage ^ 1);
-                    if (i + 1 < NBATCH) fused_load(i + 1, (kt + 1) * kSlabBytes);
+                if (more) {
+                    if (i < NBATCH) fused_store(i, a_next, b_slot ^ 1);
+                    if (i + 1 < NBATCH) fused_load(i + 1, k1);
                 }
             }
-            // first MFMA of the block, then the request for the next block's fragments, then the rest: whatever
-            // wait the compiler puts in front of the first MFMA then never covers the newest request
-            mma(fa[i & 1][0], fb[0][0], acc[i][0]);
-            __builtin_amdgcn_sched_barrier(0);
-            read_a(stage, i + 1, (i + 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int s = 0; s < KS; ++s)
 #pragma unroll
-                for (int j = 0; j < TILES_N; ++j)
-                    if (s + j > 0) mma(fa[i & 1][s], fb[s][j], acc[i][j]);
+                for (int j = 0; j < TILES_N; ++j) {
+                    const int q = s * TILES_N + j;                 // MFMA number within the block
+                    const int m = i * MMAS_PER_BLOCK + q;          // MFMA number within the step
+                    mma(fa[i & 1][s], fb[s][j], acc[i][j]);
+                    if (q == 0) {
+                        // the request for the next block's fragments follows the block's first MFMA, so that the
+                        // wait in front of that MFMA never covers the newest request
+                        __builtin_amdgcn_sched_barrier(0);
+                        read_a(a_slot, i + 1, (i + 1) & 1);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+#pragma unroll
+                    for (int c = 0; c < NC; ++c)
+                        if ((c * N1) / NC == m) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            copy_before_e(c);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                }
             __builtin_amdgcn_sched_barrier(0);
         }
-        const bool more = kt + 1 < nk;
         if (more) {
-            if constexpr (UNITS_F > 0) { if (NBATCH == BLOCKS_M) fused_store(BLOCKS_M - 1, stage ^ 1); }
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            if constexpr (UNITS_F > 0) { if (NBATCH == BLOCKS_M) fused_store(BLOCKS_M - 1, a_next, b_slot ^ 1); }
+            // E_kt
+            if (more2) wait_vm_lgkm<NA>(); else wait_vm_lgkm<0>();
             __syncthreads();
-            if (kt + 2 < nk) { issue_loads((kt + 2) * kSlabBytes, stage); fused_load(0, (kt + 2) * kSlabBytes); }
-            read_a(stage ^ 1, 0, 0);
+            if (more2) fused_load(0, k2);
+            read_a(a_next, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-        const uint8_t* sb_next = lds + (stage ^ 1) * STAGE_BYTES + b_off;
+        const uint8_t* sb_next = lds + (b_slot ^ 1) * B_SLOT + b_off;
 #pragma unroll
         for (int s = 0; s < KS; ++s)
 #pragma unroll
             for (int j = 0; j < TILES_N; ++j) {
+                const int q = s * TILES_N + j;
                 mma(fa[(BLOCKS_M - 1) & 1][s], fb[s][j], acc[BLOCKS_M - 1][j]);
                 if (more) fb[s][j] = read_frag(sb_next + j * R * kSlabBytes, s);
+#pragma unroll
+                for (int c = 0; c < NB_TAIL; ++c)
+                    if ((c * MMAS_PER_BLOCK) / (NB_TAIL > 0 ? NB_TAIL : 1) == q) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (more2) copy_b(c, k2, b_slot);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
             }
         __builtin_amdgcn_sched_barrier(0);
+        a_slot = a_next;
     }
+
+    // wait states between the last matrix instruction and the first read of an accumulator (the longest MFMA
+    // here takes 16 passes; 32 states cover every case)
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- epilogue.  MFMA result D[i][j]: i = A row within the block, j = lane % R = B row within the block.
     //  16x16: a lane's register r of acc[ia][t] is row 16*ia + 4*(l/16) + r, column TILES_N*(l%16) + t
@@ -394,14 +501,9 @@ gemm_kernel(GemmArgs g)
     // value tt of register r of A block ia, descaled: (acc * deltaA[row]) * deltaB[column], in that order
     auto value = [&](int ia, int r, int tt, float sl, uint32_t& raw) -> float {
         float a;
-        if constexpr (BLOCKS_M * TILES_N * REGS >= 256) {
-            // the large tile keeps its 256 accumulators in AGPRs: copy each one out where it is used, so that
-            // the register allocator does not try to hold all of them in VGPRs at once
-            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(raw) : "a"(acc[ia][tt][r]));
-        } else {
-            if constexpr (KIND == KIND_I8) raw = (uint32_t)acc[ia][tt][r];
-            else raw = __float_as_uint(acc[ia][tt][r]);
-        }
+        // accumulators live in AGPRs: each one is copied out where it is used (the register allocator must not
+        // try to hold all of them in VGPRs at once)
+        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(raw) : "a"(acc[ia][tt][r]));
         if constexpr (KIND == KIND_I8) a = (float)(int32_t)raw;
         else a = __uint_as_float(raw);
         if constexpr (descale) a = (a * sl) * sr[tt];
@@ -471,8 +573,7 @@ template <int KIND, int FA, int FB, int TM, int TG, int FUSE>
 qmm_status launch_tile(GemmArgs& g, hipStream_t s)
 {
     constexpr int BM = 2 * 32 * TM, BN = 2 * 64 * TG;
-    constexpr int STAGE_BYTES = (BM + BN) * kSlabBytes;
-    constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+    constexpr int LDS_BYTES = (kASlots * BM + kBSlots * BN) * kSlabBytes;
     g.tiles_m = (int)((g.M + BM - 1) / BM);
     g.tiles_n = (int)((g.N + BN - 1) / BN);
     const int64_t total = (int64_t)g.tiles_m * g.tiles_n * g.batch;
@@ -493,7 +594,8 @@ qmm_status launch_fuse(GemmArgs& g, hipStream_t s)
 {
     // 256 x 256 tiles when they still give every CU work, else 128 x 128.
     const int64_t big = ((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
-    if (big >= 192) return launch_tile<KIND, FA, FB, 4, 2, FUSE>(g, s);
+    static const int64_t thr = getenv("QMM_EXP_THR") ? atoll(getenv("QMM_EXP_THR")) : 192;  // EXPERIMENT
+    if (big >= thr) return launch_tile<KIND, FA, FB, 4, 2, FUSE>(g, s);
     return launch_tile<KIND, FA, FB, 2, 1, FUSE>(g, s);
 }
 
@@ -554,6 +656,7 @@ extern "C" qmm_status qmm_gemm(const qmm_operand* a, const qmm_operand* b, int64
     if (!bf && (!a->delta || !b->delta)) return QMM_ERR_NULL;
     const int64_t esz = bf ? 2 : 1;
     if ((K * esz) % 16 != 0) return QMM_ERR_ALIGN;
+    if (K * esz > (int64_t(1) << 22)) return QMM_ERR_UNSUPPORTED;   // the kernels keep 32-bit byte offsets within a tile's rows
     if (K > 0 && (!a->data || !b->data)) return QMM_ERR_NULL;
     if (!aligned16(a->data) || !aligned16(b->data) || (y && !aligned16(y)) || (acc_out && !aligned16(acc_out)))
         return QMM_ERR_ALIGN;
