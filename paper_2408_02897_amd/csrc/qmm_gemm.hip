@@ -47,7 +47,7 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 enum Kind { KIND_I8 = 0, KIND_F8 = 1, KIND_BF16 = 2 };
 
-constexpr int kThreads = 256;
+constexpr int kWavesM = 2;                 // wavefronts along M in a workgroup (along N: template parameter)
 constexpr int kASlots = 3, kBSlots = 2;   // LDS ring depths of the two operands
 constexpr int kSlabBytes = 128;      // K bytes per row per pipeline step = one LDS row
 constexpr int kNumXcd = 8;
@@ -99,15 +99,17 @@ template <int N> QMM_DEV void wait_vm_lgkm()
 
 // FUSE: bit 0 / bit 1 = the A / B operand arrives as bfloat16 values and is quantized (RTNE, with its step sizes)
 // while it is staged into LDS; otherwise it arrives as 8-bit codes and is copied by LDS-DMA.
-template <int KIND, int FA, int FB, int TM, int TG, int FUSE>
-__global__ void __launch_bounds__(kThreads, 1)
+// NWN: wavefronts along N (2 or 4): the workgroup has 2 x NWN wavefronts, NWN / 2 on every SIMD.
+template <int KIND, int FA, int FB, int TM, int TG, int NWN, int FUSE>
+__global__ void __launch_bounds__(64 * kWavesM * NWN, 1)
 gemm_kernel(GemmArgs g)
 {
     constexpr bool F8 = (KIND == KIND_F8);
     constexpr bool FUSE_A = (FUSE & 1) != 0, FUSE_B = (FUSE & 2) != 0;
     static_assert(FUSE == 0 || KIND != KIND_BF16, "only 8-bit operands are quantized on load");
-    constexpr int BM = 2 * 32 * TM;            // workgroup tile rows
-    constexpr int BN = 2 * 64 * TG;            // workgroup tile columns
+    constexpr int NWAVES = kWavesM * NWN;
+    constexpr int BM = kWavesM * 32 * TM;      // workgroup tile rows
+    constexpr int BN = NWN * 64 * TG;          // workgroup tile columns
     constexpr int WM = 32 * TM, WN = 64 * TG;  // wavefront tile
     constexpr int R = F8 ? 16 : 32;            // rows of one MFMA operand block
     constexpr int BLOCKS_M = WM / R;           // A blocks per wavefront
@@ -116,14 +118,14 @@ gemm_kernel(GemmArgs g)
     constexpr int A_SLOT = BM * kSlabBytes, B_SLOT = BN * kSlabBytes;   // one K slab of A / of B in LDS
     constexpr int B_BASE = kASlots * A_SLOT;                            // LDS: kASlots A slabs, then kBSlots B slabs
     constexpr int A_UNITS = BM / 8, B_UNITS = BN / 8;          // DMA units of 8 LDS rows
-    constexpr int A_PER_WAVE = A_UNITS / 4, B_PER_WAVE = B_UNITS / 4;
+    constexpr int A_PER_WAVE = A_UNITS / NWAVES, B_PER_WAVE = B_UNITS / NWAVES;
     static_assert(BLOCKS_M % 2 == 0, "A fragments ping-pong between two register sets");
     static_assert(A_PER_WAVE % 2 == 0 && B_PER_WAVE % 2 == 0, "a wavefront's units start on an even LDS row pair");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: kept in a scalar register
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / NWN, wn = wave % NWN;
 
     // ---- workgroup id -> (batch, tile_m, tile_n), XCD-aware and grouped along m
     const int64_t tiles_per_batch = (int64_t)g.tiles_m * g.tiles_n;
@@ -399,16 +401,26 @@ gemm_kernel(GemmArgs g)
     asm volatile("s_nop 7" ::: "memory");     // accumulator initialisation -> first matrix instruction
     __builtin_amdgcn_sched_barrier(0);
     int a_slot = 0;                            // kt % 3
-    for (int kt = 0; kt < nk; ++kt) {
+    // One K step.  STEADY: slabs kt+1 and kt+2 exist and are whole, so every copy is issued without a test; the
+    // code between the matrix instructions is then free of branches (a taken branch stalls the wavefront's issue
+    // for longer than a copy does).
+    auto step = [&](int kt, auto steady_tag) {
+        constexpr bool STEADY = decltype(steady_tag)::value;
         const int b_slot = kt & 1;
         const int a_next = a_slot == 2 ? 0 : a_slot + 1;          // slot of A slab kt+1
         const int a_free = a_slot == 0 ? 2 : a_slot - 1;          // slot of A slab kt+2 (slab kt-1 left it at E_(kt-1))
-        const bool more = kt + 1 < nk, more2 = kt + 2 < nk;
+        const bool more = STEADY || kt + 1 < nk, more2 = STEADY || kt + 2 < nk;
         const int k1 = (kt + 1) * kSlabBytes, k2 = (kt + 2) * kSlabBytes;
         // copy number c of the blocks before E: the rest of B slab kt+1, then A slab kt+2
         auto copy_before_e = [&](int c) {
-            if (c < NB - NB_TAIL) { if (more) copy_b(NB_TAIL + c, k1, b_slot ^ 1); }
-            else { if (more2) copy_a(c - (NB - NB_TAIL), k2, a_free); }
+            if (c < NB - NB_TAIL) {
+                if constexpr (STEADY) dma16_uniform(b_tile + k1, b_src[NB_TAIL + c], lds_b_units + (b_slot ^ 1) * B_SLOT + (NB_TAIL + c) * 1024);
+                else if (more) copy_b(NB_TAIL + c, k1, b_slot ^ 1);
+            } else {
+                const int i = c - (NB - NB_TAIL);
+                if constexpr (STEADY) dma16_uniform(a_tile + k2, a_src[i], lds_a_units + a_free * A_SLOT + i * 1024);
+                else if (more2) copy_a(i, k2, a_free);
+            }
         };
 #pragma unroll
         for (int i = 0; i < BLOCKS_M - 1; ++i) {
@@ -464,13 +476,18 @@ gemm_kernel(GemmArgs g)
                 for (int c = 0; c < NB_TAIL; ++c)
                     if ((c * MMAS_PER_BLOCK) / (NB_TAIL > 0 ? NB_TAIL : 1) == q) {
                         __builtin_amdgcn_sched_barrier(0);
-                        if (more2) copy_b(c, k2, b_slot);
+                        if constexpr (STEADY) dma16_uniform(b_tile + k2, b_src[c], lds_b_units + b_slot * B_SLOT + c * 1024);
+                        else if (more2) copy_b(c, k2, b_slot);
                         __builtin_amdgcn_sched_barrier(0);
                     }
             }
         __builtin_amdgcn_sched_barrier(0);
         a_slot = a_next;
-    }
+    };
+    const int nk_steady = rowbytes / kSlabBytes - 2;    // steps whose two following slabs are whole
+    int kt = 0;
+    for (; kt < nk_steady; ++kt) step(kt, std::true_type{});
+    for (; kt < nk; ++kt) step(kt, std::false_type{});
 
     // wait states between the last matrix instruction and the first read of an accumulator (the longest MFMA
     // here takes 16 passes; 32 states cover every case)
@@ -569,23 +586,23 @@ gemm_kernel(GemmArgs g)
     }
 }
 
-template <int KIND, int FA, int FB, int TM, int TG, int FUSE>
+template <int KIND, int FA, int FB, int TM, int TG, int NWN, int FUSE>
 qmm_status launch_tile(GemmArgs& g, hipStream_t s)
 {
-    constexpr int BM = 2 * 32 * TM, BN = 2 * 64 * TG;
+    constexpr int BM = kWavesM * 32 * TM, BN = NWN * 64 * TG;
     constexpr int LDS_BYTES = (kASlots * BM + kBSlots * BN) * kSlabBytes;
     g.tiles_m = (int)((g.M + BM - 1) / BM);
     g.tiles_n = (int)((g.N + BN - 1) / BN);
     const int64_t total = (int64_t)g.tiles_m * g.tiles_n * g.batch;
     if (total > 0x7FFFFFFF) return QMM_ERR_UNSUPPORTED;
-    auto kern = gemm_kernel<KIND, FA, FB, TM, TG, FUSE>;
+    auto kern = gemm_kernel<KIND, FA, FB, TM, TG, NWN, FUSE>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
             return QMM_ERR_LAUNCH;
         attr_set = true;
     }
-    kern<<<(unsigned)total, kThreads, LDS_BYTES, s>>>(g);
+    kern<<<(unsigned)total, 64 * kWavesM * NWN, LDS_BYTES, s>>>(g);
     return launch_status();
 }
 
@@ -595,8 +612,10 @@ qmm_status launch_fuse(GemmArgs& g, hipStream_t s)
     // 256 x 256 tiles when they still give every CU work, else 128 x 128.
     const int64_t big = ((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
     static const int64_t thr = getenv("QMM_EXP_THR") ? atoll(getenv("QMM_EXP_THR")) : 192;  // EXPERIMENT
-    if (big >= thr) return launch_tile<KIND, FA, FB, 4, 2, FUSE>(g, s);
-    return launch_tile<KIND, FA, FB, 2, 1, FUSE>(g, s);
+    static const int nwn = getenv("QMM_EXP_NWN") ? atoi(getenv("QMM_EXP_NWN")) : 2;  // EXPERIMENT
+    if (big >= thr && nwn == 4) return launch_tile<KIND, FA, FB, 4, 1, 4, FUSE>(g, s);
+    if (big >= thr) return launch_tile<KIND, FA, FB, 4, 2, 2, FUSE>(g, s);
+    return launch_tile<KIND, FA, FB, 2, 1, 2, FUSE>(g, s);
 }
 
 // fuse: bit 0 = A is quantized on load, bit 1 = B is
