@@ -31,7 +31,6 @@
 #include <type_traits>
 
 #include "qmm_device.h"
-#include <cstdlib>
 
 namespace qmm {
 namespace {
@@ -609,12 +608,11 @@ qmm_status launch_tile(GemmArgs& g, hipStream_t s)
 template <int KIND, int FA, int FB, int FUSE>
 qmm_status launch_fuse(GemmArgs& g, hipStream_t s)
 {
-    // 256 x 256 tiles when they still give every CU work, else 128 x 128.
+    // 256 x 256 tiles (eight wavefronts, two per SIMD: while one waits at a copy or a fragment read the other
+    // issues matrix instructions) when they still give every CU work, else 128 x 128 tiles (four wavefronts, two
+    // workgroups per CU).
     const int64_t big = ((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
-    static const int64_t thr = getenv("QMM_EXP_THR") ? atoll(getenv("QMM_EXP_THR")) : 192;  // EXPERIMENT
-    static const int nwn = getenv("QMM_EXP_NWN") ? atoi(getenv("QMM_EXP_NWN")) : 2;  // EXPERIMENT
-    if (big >= thr && nwn == 4) return launch_tile<KIND, FA, FB, 4, 1, 4, FUSE>(g, s);
-    if (big >= thr) return launch_tile<KIND, FA, FB, 4, 2, 2, FUSE>(g, s);
+    if (big >= 192) return launch_tile<KIND, FA, FB, 4, 1, 4, FUSE>(g, s);
     return launch_tile<KIND, FA, FB, 2, 1, 2, FUSE>(g, s);
 }
 

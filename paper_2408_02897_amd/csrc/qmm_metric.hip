@@ -11,7 +11,7 @@ namespace qmm {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxBlocks = 1024;   // 4 workgroups per CU; also 16 partials per lane in the final fold
+constexpr int kMaxBlocks = 2048;   // 8 workgroups per CU; also 32 partials per lane in the final fold
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
@@ -20,6 +20,42 @@ struct Acc {
     double s_ee = 0, s_rr = 0, s_ae = 0, s_ar = 0, m_e = 0, m_r = 0;
     double re_sum = 0, re_max = 0, be_sum = 0, be_max = 0;
     unsigned re_cnt = 0, be_cnt = 0, n = 0, nan_cnt = 0;     // a thread sees far fewer than 2^32 elements
+
+    // The common case, taken when the whole wavefront's elements are ordinary: no NaN error, r != 0 and d > 0
+    // everywhere.  Same sums as add(), without the selects and compares.
+    template <bool HAS_D> QMM_DEV void add_plain(float yf, float rf, float df)
+    {
+        const double ae = fabs((double)yf - (double)rf);
+        const double ar = fabs((double)rf);
+        s_ee = fma(ae, ae, s_ee);
+        s_rr = fma(ar, ar, s_rr);
+        s_ae += ae;
+        s_ar += ar;
+        m_e = fmax(m_e, ae);
+        m_r = fmax(m_r, ar);
+        const double q = ae / ar;
+        re_sum += q;
+        re_max = fmax(re_max, q);
+        if constexpr (HAS_D) {
+            const double qb = ae / (double)df;
+            be_sum += qb;
+            be_max = fmax(be_max, qb);
+        }
+    }
+    // counts of a run of `k` plain elements
+    template <bool HAS_D> QMM_DEV void count_plain(unsigned k)
+    {
+        re_cnt += k; n += k;
+        if constexpr (HAS_D) be_cnt += k;
+    }
+    // true if add_plain() would not give add()'s result for this element
+    template <bool HAS_D> static QMM_DEV bool special(float yf, float rf, float df)
+    {
+        const float e = yf - rf;                    // NaN exactly when the binary64 difference is NaN
+        bool sp = !(e == e) || rf == 0.0f;
+        if constexpr (HAS_D) sp = sp || !(df > 0.0f);
+        return sp;
+    }
 
     template <bool HAS_D> QMM_DEV void add(float yf, float rf, float df)
     {
@@ -105,10 +141,21 @@ metric_partial(const void* __restrict__ yv, const float* __restrict__ r, const f
         const f32x4 r0 = r4[i], r1 = r4[i + stride];
         f32x4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
         if constexpr (HAS_D) { d0 = d4[i]; d1 = d4[i + stride]; }
+        bool sp = false;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc.add<HAS_D>(y0[j], r0[j], d0[j]);
+        for (int j = 0; j < 4; ++j) sp = sp || Acc::special<HAS_D>(y0[j], r0[j], d0[j]) || Acc::special<HAS_D>(y1[j], r1[j], d1[j]);
+        if (!__any(sp)) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc.add<HAS_D>(y1[j], r1[j], d1[j]);
+            for (int j = 0; j < 4; ++j) acc.add_plain<HAS_D>(y0[j], r0[j], d0[j]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc.add_plain<HAS_D>(y1[j], r1[j], d1[j]);
+            acc.count_plain<HAS_D>(8u);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc.add<HAS_D>(y0[j], r0[j], d0[j]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc.add<HAS_D>(y1[j], r1[j], d1[j]);
+        }
     }
     if (i < nvec) {
         const f32x4 y0 = load_y4<Y_BF16>(yv, i);
@@ -138,7 +185,7 @@ metric_finalize(const double* __restrict__ partial, int nblocks, double* __restr
     const int field = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
     const bool is_max = (field == 4 || field == 5 || field == 7 || field == 10);
     const double* p = partial + (int64_t)field * nblocks;
-    // all of a lane's partials are requested before any is used (kMaxBlocks / 64 = 16 independent loads)
+    // all of a lane's partials are requested before any is used (kMaxBlocks / 64 independent loads)
     double v[kMaxBlocks / kWave];
 #pragma unroll
     for (int k = 0; k < kMaxBlocks / kWave; ++k) {
