@@ -532,13 +532,27 @@ gemm_kernel(GemmArgs g)
         // fast path: whole tile inside the matrix, bfloat16 output only; 2*TILES_N bytes per lane and store
         uint8_t* ybase = static_cast<uint8_t*>(g.y) + ((bidx * g.M + m_base) * g.N + n) * 2;
         const int64_t row_bytes = g.N * 2;
+        // Row step sizes are all fetched before the first store: loads and stores share one in-order counter, so
+        // a load issued between the stores could only be waited for together with every store before it.
+        float sl_rows[BLOCKS_M][REGS];
+#pragma unroll
+        for (int ia = 0; ia < BLOCKS_M; ++ia)
+#pragma unroll
+            for (int r = 0; r < REGS; ++r) sl_rows[ia][r] = sa_scalar;
+        if constexpr (descale) {
+            if (g.da_per_channel) {
+#pragma unroll
+                for (int ia = 0; ia < BLOCKS_M; ++ia)
+#pragma unroll
+                    for (int r = 0; r < REGS; ++r) sl_rows[ia][r] = da[m_base + ia * R + row_in_block(r)];
+            }
+        }
 #pragma unroll
         for (int ia = 0; ia < BLOCKS_M; ++ia) {
 #pragma unroll
             for (int r = 0; r < REGS; ++r) {
                 const int ml = ia * R + row_in_block(r);
-                float sl = sa_scalar;
-                if constexpr (descale) { if (g.da_per_channel) sl = da[m_base + ml]; }
+                const float sl = sl_rows[ia][r];
                 typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
                 typedef float f2 __attribute__((ext_vector_type(2)));
                 uint32_t pk[TILES_N / 2];
