@@ -122,6 +122,21 @@ def main():
                 "achieved": round(gemm_tflops, 1), "peak": PEAK[args.format], "unit": "TFLOP/s",
                 "frac": round(gemm_tflops / PEAK[args.format], 4), "traffic": None,
                 "avg_launch_ms": round(gemm_ms_per_launch, 4)}
+    # ---- what the matrix units sustain on these very codes with no memory traffic (and on constant codes): the
+    #      chip's clock under matrix load is set by power, which depends on the operand bytes
+    def mfma_only(codes):
+        ts = []
+        for _ in range(4):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); _, fl = qmm.mfma_rate(codes, fmt, fmt, rounds=100); e1.record()
+            torch.cuda.synchronize(); ts.append(e0.elapsed_time(e1))
+        return fl / (sorted(ts[1:])[1] * 1e-3) / 1e12
+    big = max(state, key=lambda st: st["cx"].numel())
+    const_code = 0x38 if fmt != qmm.INT8 else 0x40
+    mfma_codes = mfma_only(big["cx"].view(-1))
+    mfma_const = mfma_only(torch.full((1 << 20,), const_code, dtype=torch.uint8, device=dev))
+    roofline["mfma_only_tflops"] = {"workload_codes": round(mfma_codes, 1), "constant_codes": round(mfma_const, 1)}
+    roofline["frac_of_mfma_only_on_workload_codes"] = round(gemm_tflops / mfma_codes, 4)
     passes = {k: {"ms_per_step": round(per_kind_ms[k], 4),
                   "GBps": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9, 1),
                   "frac_hbm": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}

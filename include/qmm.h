@@ -178,6 +178,22 @@ size_t qmm_metric_workspace_size(int64_t n);
 qmm_status qmm_metric(const void* y, qmm_dtype y_dtype, const float* y_ref, const float* denom,
                       int64_t n, double* out16, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * qmm_mfma_rate -- measurement aid, not a step of the method: the rate the matrix units sustain on given operand
+ * bytes with no memory traffic, against which the GEMM's rate is read (next to the datasheet peak, which is quoted
+ * at the top clock; under matrix load the clock is set by power, and that depends on the operand bytes).
+ *   operand_bytes device, 32-byte aligned, nbytes >= 32: 8-bit codes in the given formats (e.g. the codes
+ *                 qmm_quantize wrote); every lane takes ten fragments from it.  Not modified.
+ *   rounds        every wavefront issues rounds * 64 (FP8) or rounds * 16 (INT8) matrix instructions
+ *   workgroups    number of workgroups of four wavefronts (one per CU fills the chip)
+ *   sink          device, workgroups * 256 floats, written (keeps the work alive); caller-owned
+ *   flops_out     host: operations the launch performs (2 per multiply-add)
+ * Asynchronous on `stream`; the caller times it.  Formats: both INT8, or any pair of E4M3 / E5M2.
+ * Errors: QMM_ERR_NULL, QMM_ERR_ENUM, QMM_ERR_UNSUPPORTED, QMM_ERR_SHAPE, QMM_ERR_ALIGN, QMM_ERR_LAUNCH.
+ */
+qmm_status qmm_mfma_rate(qmm_format a_format, qmm_format b_format, const void* operand_bytes, int64_t nbytes,
+                         int64_t rounds, int32_t workgroups, float* sink, double* flops_out, void* stream);
+
 const char* qmm_status_string(qmm_status s);
 /* Version of this ABI (major*100 + minor). */
 int qmm_version(void);

@@ -14,7 +14,7 @@ DT_BF16, DT_F32 = 0, 1
 RTNE, STOCHASTIC = 0, 1
 FORMATS = {"int8": INT8, "e4m3": E4M3, "e5m2": E5M2, "bf16": BF16}
 EXPORTS = ["qmm_num_scales", "qmm_scale_workspace_size", "qmm_scale", "qmm_quantize", "qmm_gemm_workspace_size",
-           "qmm_gemm", "qmm_metric_workspace_size", "qmm_metric", "qmm_status_string", "qmm_version"]
+           "qmm_gemm", "qmm_metric_workspace_size", "qmm_metric", "qmm_mfma_rate", "qmm_status_string", "qmm_version"]
 
 
 class QmmError(RuntimeError):
@@ -59,6 +59,8 @@ def lib():
         L.qmm_gemm.restype = i32; L.qmm_gemm.argtypes = [OP, OP, i64, i64, i64, i64, vp, i32, vp, vp, sz, vp]
         L.qmm_metric_workspace_size.restype = sz; L.qmm_metric_workspace_size.argtypes = [i64]
         L.qmm_metric.restype = i32; L.qmm_metric.argtypes = [vp, i32, vp, vp, i64, vp, vp, sz, vp]
+        L.qmm_mfma_rate.restype = i32
+        L.qmm_mfma_rate.argtypes = [i32, i32, vp, i64, i64, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.qmm_status_string.restype = ctypes.c_char_p; L.qmm_status_string.argtypes = [i32]
         L.qmm_version.restype = i32; L.qmm_version.argtypes = []
         _lib = L
@@ -192,6 +194,19 @@ def metric(y, y_ref, denom=None, out=None, workspace=None):
     _check(L.qmm_metric(y.data_ptr(), _dtype_code(y), y_ref.data_ptr(), denom.data_ptr() if denom is not None else None,
                         n, out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()), "qmm_metric")
     return out
+
+
+def mfma_rate(codes, fmt_a, fmt_b, rounds=2000, workgroups=None):
+    """qmm_mfma_rate on the bytes of the uint8 device tensor `codes`; returns (sink tensor, operations launched)."""
+    L = lib()
+    assert codes.dtype == torch.uint8 and codes.is_contiguous() and codes.is_cuda
+    if workgroups is None:
+        workgroups = torch.cuda.get_device_properties(codes.device).multi_processor_count
+    sink = torch.empty(workgroups * 256, dtype=torch.float32, device=codes.device)
+    flops = ctypes.c_double(0.0)
+    _check(L.qmm_mfma_rate(fmt_a, fmt_b, codes.data_ptr(), codes.numel(), int(rounds), int(workgroups), sink.data_ptr(),
+                           ctypes.byref(flops), _stream()), "qmm_mfma_rate")
+    return sink, flops.value
 
 
 METRIC_FIELDS = ("S_ee", "S_rr", "S_ae", "S_ar", "M_e", "M_r", "RE_sum", "RE_max", "RE_cnt",
