@@ -3,7 +3,7 @@
 // element-wise backward error of Eq. 3.  HBM-bound: 8 B per element for a
 // binary32 y (6 B for bfloat16 y, +4 B with denominators).  Every thread keeps
 // private sums, wavefronts fold them by shuffles, workgroups through LDS, and a
-// one-workgroup second kernel folds the per-workgroup partials in a fixed order:
+// small second kernel (one workgroup per field) folds the per-workgroup partials in a fixed order:
 // no atomics, so the result is reproducible run to run.
 #include "qmm_device.h"
 
@@ -11,7 +11,7 @@ namespace qmm {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxBlocks = 2048;   // 8 workgroups per CU; also 32 partials per lane in the final fold
+constexpr int kMaxBlocks = 2048;   // 8 workgroups per CU; also 8 partials per thread in the final fold
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
@@ -176,27 +176,35 @@ metric_partial(const void* __restrict__ yv, const float* __restrict__ r, const f
     store_partial(acc, partial, (int)gridDim.x);
 }
 
-// One workgroup of 16 wavefronts: wavefront f folds field f over the workgroup partials.  Lane l takes blocks
-// l, l+64, ... in ascending order, then the 64 lane values are folded by the fixed shuffle tree: the order of
-// additions depends on nblocks only, so results are reproducible run to run.
-__global__ void __launch_bounds__(1024)
+// Sixteen workgroups, one per field: thread t takes blocks t, t+256, ... in ascending order, the 64 lane values
+// are folded by the fixed shuffle tree and the four wavefront values in wavefront order: the order of additions
+// depends on nblocks only, so results are reproducible run to run.
+constexpr int kFinalThreads = 256;
+__global__ void __launch_bounds__(kFinalThreads)
 metric_finalize(const double* __restrict__ partial, int nblocks, double* __restrict__ out)
 {
-    const int field = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+    __shared__ double s[kFinalThreads / kWave];
+    const int field = blockIdx.x, lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
     const bool is_max = (field == 4 || field == 5 || field == 7 || field == 10);
     const double* p = partial + (int64_t)field * nblocks;
-    // all of a lane's partials are requested before any is used (kMaxBlocks / 64 independent loads)
-    double v[kMaxBlocks / kWave];
+    // all of a thread's partials are requested before any is used
+    double v[kMaxBlocks / kFinalThreads];
 #pragma unroll
-    for (int k = 0; k < kMaxBlocks / kWave; ++k) {
-        const int b = lane + k * kWave;
+    for (int k = 0; k < kMaxBlocks / kFinalThreads; ++k) {
+        const int b = threadIdx.x + k * kFinalThreads;
         v[k] = b < nblocks ? p[b] : 0.0;
     }
     double r = 0.0;
 #pragma unroll
-    for (int k = 0; k < kMaxBlocks / kWave; ++k) r = is_max ? fmax(r, v[k]) : r + v[k];
+    for (int k = 0; k < kMaxBlocks / kFinalThreads; ++k) r = is_max ? fmax(r, v[k]) : r + v[k];
     r = is_max ? wave_max_f64(r) : wave_sum_f64(r);
-    if (lane == 0) out[field] = r;
+    if (lane == 0) s[w] = r;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = s[0];
+        for (int k = 1; k < kFinalThreads / kWave; ++k) t = is_max ? fmax(t, s[k]) : t + s[k];
+        out[field] = t;
+    }
 }
 
 int plan_blocks(int64_t n)
@@ -240,6 +248,6 @@ extern "C" qmm_status qmm_metric(const void* y, qmm_dtype y_dtype, const float* 
     else if (hd) metric_partial<false, true><<<nb, kThreads, 0, s>>>(y, y_ref, denom, n, partial);
     else metric_partial<false, false><<<nb, kThreads, 0, s>>>(y, y_ref, denom, n, partial);
     if (hipGetLastError() != hipSuccess) return QMM_ERR_LAUNCH;
-    metric_finalize<<<1, 1024, 0, s>>>(partial, nb, out16);
+    metric_finalize<<<16, kFinalThreads, 0, s>>>(partial, nb, out16);
     return launch_status();
 }
