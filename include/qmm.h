@@ -149,8 +149,14 @@ typedef struct {
  *              binary32) or NULL.
  *   K must be a multiple of 16 bytes' worth of elements (16 codes / 8 bf16)
  *   and all data pointers 16-byte aligned, else QMM_ERR_ALIGN.
- *   workspace  device scratch of at least qmm_gemm_workspace_size() bytes
- *              (may be 0, then NULL is accepted).
+ *   K in bytes (K codes, or 2 K for BF16) must not exceed 2^22, else
+ *   QMM_ERR_UNSUPPORTED.
+ *   workspace  device scratch of at least qmm_gemm_workspace_size() bytes,
+ *              16-byte aligned (may be 0, then NULL is accepted).  It is non-zero
+ *              for small outputs with a long K (weight-gradient shapes): K is
+ *              then split into ranges whose partial accumulators are kept there
+ *              and added in ascending order by a second kernel, so results do
+ *              not depend on timing.  Too small: QMM_ERR_WORKSPACE.
  */
 size_t qmm_gemm_workspace_size(const qmm_operand* a, const qmm_operand* b,
                                int64_t batch, int64_t M, int64_t N, int64_t K);

@@ -63,6 +63,8 @@ struct GemmArgs {
     void* y; int y_bf16;              // may be null
     void* acc_out;                    // may be null
     int tiles_m, tiles_n;
+    int splits;                       // split-K: workgroups per output tile (1 = none); partial sums go to `partial`
+    void* partial;                    // [splits][batch][M][N] raw accumulators (int32 / float)
 };
 
 // 16 bytes per lane from global memory into LDS: lane l lands at lds_unit + 16*l.
@@ -128,7 +130,8 @@ gemm_kernel(GemmArgs g)
 
     // ---- workgroup id -> (batch, tile_m, tile_n), XCD-aware and grouped along m
     const int64_t tiles_per_batch = (int64_t)g.tiles_m * g.tiles_n;
-    const int64_t total = tiles_per_batch * g.batch;
+    const int64_t total_tiles = tiles_per_batch * g.batch;
+    const int64_t total = total_tiles * g.splits;
     int64_t pid = blockIdx.x;
     {
         const int64_t per = (total + kNumXcd - 1) / kNumXcd, tall = total % kNumXcd;
@@ -137,6 +140,9 @@ gemm_kernel(GemmArgs g)
     }
     // the divisions run on the vector unit; their results are the same in every lane and are moved to scalar
     // registers, so that everything derived from them (tile base addresses above all) is scalar as well
+    // split-K: consecutive workgroups (same XCD) work on neighbouring tiles of the same K range
+    const int split = __builtin_amdgcn_readfirstlane((int)(pid / total_tiles));
+    pid -= split * total_tiles;
     const int64_t bidx = __builtin_amdgcn_readfirstlane((int)(pid / tiles_per_batch));
     const int64_t t = pid - bidx * tiles_per_batch;
     constexpr int GROUP_M = 8;
@@ -157,8 +163,17 @@ gemm_kernel(GemmArgs g)
     //      output column  WN*(p/WN) + TILES_N*(p%R) + (p/R)%TILES_N : MFMA block t, lane j  <->  column TILES_N*j + t,
     //      so that in the accumulators a lane owns TILES_N consecutive columns of a row.
     //      Sources are kept as 32-bit byte offsets from the tile's first A / B row.
-    const uint8_t* a_tile = A + m0 * g.rowbytes * A_ES;
-    const uint8_t* b_tile = B + n0 * g.rowbytes * B_ES;
+    // K range of this workgroup in bytes of codes: whole slabs, the last split takes the ragged end
+    int k_begin = 0, k_end = (int)g.rowbytes;
+    if (g.splits > 1) {
+        const int nslabs = ((int)g.rowbytes + kSlabBytes - 1) / kSlabBytes;
+        const int base = nslabs / g.splits, rem = nslabs % g.splits;
+        const int first = split * base + min(split, rem);
+        k_begin = first * kSlabBytes;
+        k_end = min((int)g.rowbytes, (first + base + (split < rem ? 1 : 0)) * kSlabBytes);
+    }
+    const uint8_t* a_tile = A + (m0 * g.rowbytes + k_begin) * A_ES;
+    const uint8_t* b_tile = B + (n0 * g.rowbytes + k_begin) * B_ES;
     uint32_t a_src[A_PER_WAVE], b_src[B_PER_WAVE];
     const int lane_chunk_base = lane & 7;
 #pragma unroll
@@ -184,7 +199,7 @@ gemm_kernel(GemmArgs g)
     const uint32_t lds_b_units = (uint32_t)(uintptr_t)(lds_ptr_t)(lds + B_BASE + wave * B_PER_WAVE * 1024);
     // A partial last slab (K not a multiple of the slab width): lanes whose 16-byte chunk lies past the end of the
     // row write zeros to their place in LDS, the others copy as usual with those lanes masked off.
-    const int rowbytes = (int)g.rowbytes;      // at most 2^22, checked on the host
+    const int rowbytes = k_end - k_begin;       // bytes of K this workgroup contracts over (g.rowbytes <= 2^22: host check)
     auto copy_unit = [&](const uint8_t* base, uint32_t lane_offset, uint32_t lds_unit_addr, uint8_t* lds_unit, int chunk,
                          int k0) {
         if (k0 + kSlabBytes <= rowbytes) {
@@ -244,7 +259,7 @@ gemm_kernel(GemmArgs g)
                     const int p = (wave * (is_a ? A_PER_WAVE : B_PER_WAVE) + i) * 8 + (lane >> 3);
                     const int c = lane_chunk_base ^ ((p >> 1) & 7);
                     const uint8_t* src = (is_a ? a_tile + a_src[i] : b_tile + b_src[i]) + k0 * 2;
-                    if (k0 + c * 16 < g.rowbytes) {
+                    if (k0 + c * 16 < rowbytes) {
                         f_raw[u][0] = reinterpret_cast<const u32x4*>(src)[0];
                         f_raw[u][1] = reinterpret_cast<const u32x4*>(src)[1];
                     } else {
@@ -528,7 +543,35 @@ gemm_kernel(GemmArgs g)
     auto row_in_block = [&](int r) -> int { return F8 ? lane_row + r : 8 * (r >> 2) + lane_row + (r & 3); };
 
     const bool interior = (m0 + BM <= g.M) && (n0 + BN <= g.N) && (g.N % TILES_N == 0);
-    if (interior && g.y && g.y_bf16 && !g.acc_out) {
+    if (g.splits > 1) {
+        // split-K: the raw accumulators of this K range go to the partial-sum buffer; a second kernel adds the
+        // ranges in ascending order, descales and writes the outputs
+        uint32_t* pbase = static_cast<uint32_t*>(g.partial) + ((int64_t)split * g.batch + bidx) * g.M * g.N;
+#pragma unroll
+        for (int ia = 0; ia < BLOCKS_M; ++ia) {
+#pragma unroll
+            for (int r = 0; r < REGS; ++r) {
+                const int64_t m = m_base + ia * R + row_in_block(r);
+                uint32_t raw[TILES_N];
+#pragma unroll
+                for (int tt = 0; tt < TILES_N; ++tt) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(raw[tt]) : "a"(acc[ia][tt][r]));
+                uint32_t* dst = pbase + m * g.N + n;
+                if (interior) {
+                    if constexpr (TILES_N == 4) *reinterpret_cast<u32x4*>(dst) = u32x4{raw[0], raw[1], raw[2], raw[3]};
+                    else if constexpr (TILES_N == 2) *reinterpret_cast<u32x2*>(dst) = u32x2{raw[0], raw[1]};
+                    else {
+#pragma unroll
+                        for (int tt = 0; tt < TILES_N; ++tt) dst[tt] = raw[tt];
+                    }
+                } else if (m < g.M) {
+#pragma unroll
+                    for (int tt = 0; tt < TILES_N; ++tt)
+                        if (n + tt < g.N) dst[tt] = raw[tt];
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else if (interior && g.y && g.y_bf16 && !g.acc_out) {
         // fast path: whole tile inside the matrix, bfloat16 output only; 2*TILES_N bytes per lane and store
         uint8_t* ybase = static_cast<uint8_t*>(g.y) + ((bidx * g.M + m_base) * g.N + n) * 2;
         const int64_t row_bytes = g.N * 2;
@@ -599,6 +642,73 @@ gemm_kernel(GemmArgs g)
     }
 }
 
+// Second kernel of split-K: out = descale(sum over the K ranges, in ascending order, of the partial accumulators).
+// INT8 partials are integers (the sum is exact); FP8 / bfloat16 partials are binary32 and added in binary32.
+// One thread per four consecutive columns.
+template <int KIND>
+__global__ void __launch_bounds__(256)
+splitk_reduce(GemmArgs g)
+{
+    const int64_t quads_per_row = (g.N + 3) / 4;
+    const int64_t total = g.batch * g.M * quads_per_row;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= total) return;
+    const int64_t row = id / quads_per_row, n = (id - row * quads_per_row) * 4;     // row = b * M + m
+    const int64_t bidx = row / g.M, m = row - bidx * g.M;
+    const int64_t plane = g.batch * g.M * g.N;
+    const bool full = (n + 4 <= g.N) && (g.N % 4 == 0);
+    int32_t si[4] = {0, 0, 0, 0};
+    float sf[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int sp = 0; sp < g.splits; ++sp) {
+        const uint32_t* p = static_cast<const uint32_t*>(g.partial) + sp * plane + row * g.N + n;
+        uint32_t v[4] = {0u, 0u, 0u, 0u};
+        if (full) {
+            const u32x4 q = *reinterpret_cast<const u32x4*>(p);
+            v[0] = q[0]; v[1] = q[1]; v[2] = q[2]; v[3] = q[3];
+        } else {
+            for (int e = 0; e < 4; ++e)
+                if (n + e < g.N) v[e] = p[e];
+        }
+        for (int e = 0; e < 4; ++e) {
+            if constexpr (KIND == KIND_I8) si[e] += (int32_t)v[e];
+            else sf[e] = sp == 0 ? __uint_as_float(v[e]) : sf[e] + __uint_as_float(v[e]);
+        }
+    }
+    float sl = 1.0f;
+    if constexpr (KIND != KIND_BF16) sl = g.da[(bidx % g.da_groups) * (g.da_per_channel ? g.M : 1) + (g.da_per_channel ? m : 0)];
+    for (int e = 0; e < 4; ++e) {
+        if (n + e >= g.N) break;
+        float a;
+        uint32_t raw;
+        if constexpr (KIND == KIND_I8) { raw = (uint32_t)si[e]; a = (float)si[e]; }
+        else { raw = __float_as_uint(sf[e]); a = sf[e]; }
+        if constexpr (KIND != KIND_BF16) {
+            const float sr = g.db[(bidx % g.db_groups) * (g.db_per_channel ? g.N : 1) + (g.db_per_channel ? n + e : 0)];
+            a = (a * sl) * sr;
+        }
+        const int64_t o = row * g.N + n + e;
+        if (g.acc_out) static_cast<uint32_t*>(g.acc_out)[o] = raw;
+        if (g.y) {
+            if (g.y_bf16) static_cast<__bf16*>(g.y)[o] = (__bf16)a;
+            else static_cast<float*>(g.y)[o] = a;
+        }
+    }
+}
+
+// Split-K plan: used when even 128 x 128 tiles would leave CUs idle and K is long (weight-gradient
+// shapes: small output, contraction over all tokens).  Returns the number of K ranges (1 = no split).
+int plan_splits(int64_t M, int64_t N, int64_t rowbytes, int64_t batch, int fuse)
+{
+    if (fuse != 0) return 1;
+    const int64_t big = ((M + 255) / 256) * ((N + 255) / 256) * batch;
+    const int64_t small = ((M + 127) / 128) * ((N + 127) / 128) * batch;
+    const int64_t nslabs = (rowbytes + kSlabBytes - 1) / kSlabBytes;
+    if (small >= 192 || nslabs < 16) return 1;       // 128 x 128 tiles fill the chip: cheaper than a second pass
+    int64_t splits = 256 / big;
+    if (splits > nslabs / 8) splits = nslabs / 8;      // at least eight slabs per range
+    return splits >= 2 ? (int)splits : 1;
+}
+
 template <int KIND, int FA, int FB, int TM, int TG, int NWN, int FUSE>
 qmm_status launch_tile(GemmArgs& g, hipStream_t s)
 {
@@ -606,7 +716,7 @@ qmm_status launch_tile(GemmArgs& g, hipStream_t s)
     constexpr int LDS_BYTES = (kASlots * BM + kBSlots * BN) * kSlabBytes;
     g.tiles_m = (int)((g.M + BM - 1) / BM);
     g.tiles_n = (int)((g.N + BN - 1) / BN);
-    const int64_t total = (int64_t)g.tiles_m * g.tiles_n * g.batch;
+    const int64_t total = (int64_t)g.tiles_m * g.tiles_n * g.batch * g.splits;
     if (total > 0x7FFFFFFF) return QMM_ERR_UNSUPPORTED;
     auto kern = gemm_kernel<KIND, FA, FB, TM, TG, NWN, FUSE>;
     static bool attr_set = false;
@@ -616,6 +726,11 @@ qmm_status launch_tile(GemmArgs& g, hipStream_t s)
         attr_set = true;
     }
     kern<<<(unsigned)total, 64 * kWavesM * NWN, LDS_BYTES, s>>>(g);
+    if (g.splits > 1) {
+        if (hipGetLastError() != hipSuccess) return QMM_ERR_LAUNCH;
+        const int64_t threads = g.batch * g.M * ((g.N + 3) / 4);
+        splitk_reduce<KIND><<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(g);
+    }
     return launch_status();
 }
 
@@ -626,7 +741,7 @@ qmm_status launch_fuse(GemmArgs& g, hipStream_t s)
     // issues matrix instructions) when they still give every CU work, else 128 x 128 tiles (four wavefronts, two
     // workgroups per CU).
     const int64_t big = ((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
-    if (big >= 192) return launch_tile<KIND, FA, FB, 4, 1, 4, FUSE>(g, s);
+    if (big >= 192 || g.splits > 1) return launch_tile<KIND, FA, FB, 4, 1, 4, FUSE>(g, s);
     return launch_tile<KIND, FA, FB, 2, 1, 2, FUSE>(g, s);
 }
 
@@ -662,16 +777,20 @@ qmm_status check_operand(const qmm_operand* o)
 
 using namespace qmm;
 
-extern "C" size_t qmm_gemm_workspace_size(const qmm_operand*, const qmm_operand*, int64_t, int64_t, int64_t, int64_t)
+extern "C" size_t qmm_gemm_workspace_size(const qmm_operand* a, const qmm_operand* b, int64_t batch, int64_t M, int64_t N,
+                                          int64_t K)
 {
-    return 0;
+    if (!a || !b || batch <= 0 || M <= 0 || N <= 0 || K <= 0) return 0;
+    const bool bf = a->format == QMM_FMT_BF16;
+    const int fuse = bf ? 0 : ((a->is_codes ? 0 : 1) | (b->is_codes ? 0 : 2));
+    const int splits = plan_splits(M, N, K * (bf ? 2 : 1), batch, fuse);
+    return splits > 1 ? (size_t)splits * (size_t)batch * (size_t)M * (size_t)N * 4u : 0;
 }
 
 extern "C" qmm_status qmm_gemm(const qmm_operand* a, const qmm_operand* b, int64_t batch, int64_t M, int64_t N, int64_t K,
                                void* y, qmm_dtype y_dtype, void* acc_out, void* workspace, size_t workspace_bytes,
                                void* stream)
 {
-    (void)workspace; (void)workspace_bytes;
     qmm_status st = check_operand(a);
     if (st != QMM_OK) return st;
     st = check_operand(b);
@@ -699,6 +818,13 @@ extern "C" qmm_status qmm_gemm(const qmm_operand* a, const qmm_operand* b, int64
     g.da_groups = a->gran.batch_groups; g.db_groups = b->gran.batch_groups;
     g.da_per_channel = a->gran.per_channel; g.db_per_channel = b->gran.per_channel;
     g.y = y; g.y_bf16 = y_dtype == QMM_DT_BF16; g.acc_out = acc_out;
+    g.splits = plan_splits(M, N, g.rowbytes, batch, fuse);
+    if (g.splits > 1) {
+        const size_t need = (size_t)g.splits * (size_t)batch * (size_t)M * (size_t)N * 4u;
+        if (!workspace || workspace_bytes < need) return QMM_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return QMM_ERR_ALIGN;
+        g.partial = workspace;
+    }
     hipStream_t s = as_stream(stream);
 
     if (bf) return launch_kind<KIND_BF16, QMM_FMT_BF16, QMM_FMT_BF16>(g, s, 0);

@@ -159,7 +159,9 @@ def _random_codes(fmt, shape, seed):
 
 
 GEMM_SHAPES = [(1, 16, 16, 16), (1, 128, 128, 128), (1, 256, 768, 768), (1, 200, 136, 400), (1, 300, 272, 144),
-               (3, 130, 80, 64), (1, 520, 528, 1040), (2, 257, 512, 272), (1, 64, 1000, 48)]
+               (3, 130, 80, 64), (1, 520, 528, 1040), (2, 257, 512, 272), (1, 64, 1000, 48),
+               # long K, few tiles: the split-K path (partial sums per K range, reduced in a fixed order)
+               (1, 64, 96, 4096), (2, 100, 72, 2064), (1, 300, 272, 2048)]
 
 
 @pytest.mark.parametrize("shape", GEMM_SHAPES)
@@ -299,7 +301,7 @@ def test_gemm_quantize_on_load_matches_separate_quantize(shape, fa, fb, per_chan
 
 
 def test_reference_gemm():
-    for (bt, M, N, K) in [(1, 256, 768, 768), (2, 100, 72, 200), (1, 130, 258, 520)]:
+    for (bt, M, N, K) in [(1, 256, 768, 768), (2, 100, 72, 200), (1, 130, 258, 520), (1, 200, 264, 4104)]:   # last: split-K
         x = W.normal((bt, M, K), 1.0, 5); w = W.normal((bt, N, K), 0.02, 6)
         r = qmm.reference_gemm(x.to(DEV), w.to(DEV)).cpu().numpy()
         want = O.ref_gemm(np32(x), np32(w))
