@@ -461,7 +461,7 @@ gemm_kernel(GemmArgs g)
                     }
 #pragma unroll
                     for (int c = 0; c < NC; ++c)
-                        if ((c * N1) / NC == m) {
+                        if ((c * N1) / (NC > 0 ? NC : 1) == m) {
                             __builtin_amdgcn_sched_barrier(0);
                             copy_before_e(c);
                             __builtin_amdgcn_sched_barrier(0);
@@ -612,8 +612,41 @@ gemm_kernel(GemmArgs g)
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+    } else if (interior && g.y && !g.y_bf16 && !g.acc_out && TILES_N % 4 == 0) {
+        // whole tile inside the matrix, binary32 output only: 16 bytes per store
+        float* ybase = static_cast<float*>(g.y) + (bidx * g.M + m_base) * g.N + n;
+        float sl_rows[BLOCKS_M][REGS];
+#pragma unroll
+        for (int ia = 0; ia < BLOCKS_M; ++ia)
+#pragma unroll
+            for (int r = 0; r < REGS; ++r) sl_rows[ia][r] = sa_scalar;
+        if constexpr (descale) {
+            if (g.da_per_channel) {
+#pragma unroll
+                for (int ia = 0; ia < BLOCKS_M; ++ia)
+#pragma unroll
+                    for (int r = 0; r < REGS; ++r) sl_rows[ia][r] = da[m_base + ia * R + row_in_block(r)];
+            }
+        }
+#pragma unroll
+        for (int ia = 0; ia < BLOCKS_M; ++ia) {
+#pragma unroll
+            for (int r = 0; r < REGS; ++r) {
+                const int ml = ia * R + row_in_block(r);
+                float* dst = ybase + (int64_t)ml * g.N;
+#pragma unroll
+                for (int q = 0; q < TILES_N / 4; ++q) {
+                    uint32_t raw;
+                    v4f v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = value(ia, r, 4 * q + e, sl_rows[ia][r], raw);
+                    *reinterpret_cast<v4f*>(dst + 4 * q) = v;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     } else if (n < g.N) {
-        // general path: edge tiles, float output, raw accumulators; element-wise with bounds checks
+        // general path: edge tiles, raw accumulators, narrow lanes; element-wise with bounds checks
 #pragma unroll
         for (int ia = 0; ia < BLOCKS_M; ++ia) {
 #pragma unroll
@@ -741,7 +774,9 @@ qmm_status launch_fuse(GemmArgs& g, hipStream_t s)
     // issues matrix instructions) when they still give every CU work, else 128 x 128 tiles (four wavefronts, two
     // workgroups per CU).
     const int64_t big = ((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
-    if (big >= 192 || g.splits > 1) return launch_tile<KIND, FA, FB, 4, 1, 4, FUSE>(g, s);
+    // an output narrower than half a big tile wastes less of a small one
+    const bool narrow = g.M <= 128 || g.N <= 128;
+    if ((big >= 192 && !narrow) || g.splits > 1) return launch_tile<KIND, FA, FB, 4, 1, 4, FUSE>(g, s);
     return launch_tile<KIND, FA, FB, 2, 1, 2, FUSE>(g, s);
 }
 
