@@ -22,6 +22,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM bytes per GEMM launch (mean of the four launches of a step) from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
+# very command, scaled by what the same counters read for a plain 256 MiB copy (factors 2.00 and 1.00); the summary
+# with the commands is profiles/bench_bert_large_fwd_e4m3.md.  Other workloads / formats: not collected (null).
+GEMM_TRAFFIC = {("bert_large_fwd", "e4m3"): {"read_bytes": 75.8e6, "write_bytes": 75.5e6,
+                                             "algorithmic_read_bytes": 32.4e6, "algorithmic_write_bytes": 75.4e6}}
 PEAK = {"e4m3": 5000.0, "e5m2": 5000.0, "int8": 5000.0}   # dense MFMA TFLOP/s (TOP/s), MI355X
 HBM_PEAK_GBS = 8000.0
 
@@ -127,21 +132,32 @@ def main():
     gemm_tflops = flops / (per_kind_ms["gemm"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "gemm_kernel (fp8/int8 MFMA, 4 launches per step)",
                 "achieved": round(gemm_tflops, 1), "peak": PEAK[args.format], "unit": "TFLOP/s",
-                "frac": round(gemm_tflops / PEAK[args.format], 4), "traffic": None,
+                "frac": round(gemm_tflops / PEAK[args.format], 4),
+                "traffic": GEMM_TRAFFIC.get((args.workload, args.format)),
                 "avg_launch_ms": round(gemm_ms_per_launch, 4)}
     # ---- what the matrix units sustain on these very codes with no memory traffic (and on constant codes): the
     #      chip's clock under matrix load is set by power, which depends on the operand bytes
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty(n_cu * 256, dtype=torch.float32, device=dev)
+
     def mfma_only(codes):
         ts = []
-        for _ in range(4):
+        for _ in range(4):       # about 1 ms each, so that dispatch latency does not count
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(); _, fl = qmm.mfma_rate(codes, fmt, fmt, rounds=100); e1.record()
+            e0.record(); _, fl = qmm.mfma_rate(codes, fmt, fmt, rounds=1000, workgroups=n_cu, sink=sink); e1.record()
             torch.cuda.synchronize(); ts.append(e0.elapsed_time(e1))
         return fl / (sorted(ts[1:])[1] * 1e-3) / 1e12
     big = max(state, key=lambda st: st["cx"].numel())
     const_code = 0x38 if fmt != qmm.INT8 else 0x40
     mfma_codes = mfma_only(big["cx"].view(-1))
     mfma_const = mfma_only(torch.full((1 << 20,), const_code, dtype=torch.uint8, device=dev))
+    # stream time an event pair adds around a launch (dispatch latency): a pair around a one-element kernel
+    tiny = torch.zeros(1, device=dev)
+    ov = []
+    for _ in range(20):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); tiny.add_(1.0); e1.record(); torch.cuda.synchronize(); ov.append(e0.elapsed_time(e1))
+    roofline["event_pair_around_one_element_kernel_ms"] = round(sorted(ov)[len(ov) // 2], 4)
     roofline["mfma_only_tflops"] = {"workload_codes": round(mfma_codes, 1), "constant_codes": round(mfma_const, 1)}
     roofline["frac_of_mfma_only_on_workload_codes"] = round(gemm_tflops / mfma_codes, 4)
     passes = {k: {"ms_per_step": round(per_kind_ms[k], 4),

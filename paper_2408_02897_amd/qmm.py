@@ -196,13 +196,15 @@ def metric(y, y_ref, denom=None, out=None, workspace=None):
     return out
 
 
-def mfma_rate(codes, fmt_a, fmt_b, rounds=2000, workgroups=None):
+def mfma_rate(codes, fmt_a, fmt_b, rounds=2000, workgroups=None, sink=None):
     """qmm_mfma_rate on the bytes of the uint8 device tensor `codes`; returns (sink tensor, operations launched)."""
     L = lib()
     assert codes.dtype == torch.uint8 and codes.is_contiguous() and codes.is_cuda
     if workgroups is None:
         workgroups = torch.cuda.get_device_properties(codes.device).multi_processor_count
-    sink = torch.empty(workgroups * 256, dtype=torch.float32, device=codes.device)
+    if sink is None:
+        sink = torch.empty(workgroups * 256, dtype=torch.float32, device=codes.device)
+    assert sink.numel() >= workgroups * 256 and sink.dtype == torch.float32
     flops = ctypes.c_double(0.0)
     _check(L.qmm_mfma_rate(fmt_a, fmt_b, codes.data_ptr(), codes.numel(), int(rounds), int(workgroups), sink.data_ptr(),
                            ctypes.byref(flops), _stream()), "qmm_mfma_rate")
