@@ -118,3 +118,16 @@ def attention_operands(batch=32, heads=16, seq=512, dim=64, config=5):
 def softmax_probabilities(scores_ref, dim):
     """P = softmax(S / sqrt(dim)) row-wise from reference scores (harness code, float32 -> bfloat16)."""
     return torch.softmax(scores_ref.float() / math.sqrt(dim), dim=-1).to(torch.bfloat16)
+
+
+# Degrees of freedom swept in the backward-error example (Eq. 3): heavy tails (1 = Cauchy) to normal (None).
+BACKWARD_ERROR_DOFS = (1, 2, 3, 4, 6, 10, 30, None)
+
+
+def backward_error_operands(dof, n=512):
+    """The two n x n operands of the backward-error example: Student-t with `dof` degrees of freedom (None:
+    normal), both stored with the contracting axis contiguous (L [M, K], R [N, K]: the product is L R^T)."""
+    tag = 0 if dof is None else int(dof)
+    if dof is None:
+        return normal((n, n), 1.0, 60100 + tag), normal((n, n), 1.0, 60200 + tag)
+    return student_t((n, n), dof, 60100 + tag), student_t((n, n), dof, 60200 + tag)
