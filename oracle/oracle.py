@@ -68,6 +68,8 @@ def lib():
         L.orc_ref_gemm.argtypes = [vp, vp, i64, i64, i64, i64, vp]
         L.orc_metric.restype = None
         L.orc_metric.argtypes = [vp, vp, vp, i64, vp]
+        L.orc_moments.restype = None
+        L.orc_moments.argtypes = [vp, i64, vp]
         _lib = L
     return _lib
 
@@ -233,6 +235,17 @@ def metric(y, r, d=None):
         assert d.size == y.size
     out = np.empty(16, dtype=np.float64)
     lib().orc_metric(_p(y), _p(r), _p(d) if d is not None else None, y.size, _p(out))
+    return out
+
+
+MOMENT_FIELDS = ("n", "mean", "m2", "m3", "m4", "absmax", "nan_cnt", "rsv")
+
+
+def moments(x):
+    """Population moments about the mean of all elements of x (two passes, binary64): 8 doubles, MOMENT_FIELDS."""
+    x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    out = np.empty(8, dtype=np.float64)
+    lib().orc_moments(_p(x), x.size, _p(out))
     return out
 
 

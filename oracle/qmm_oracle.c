@@ -482,3 +482,34 @@ void orc_metric(const float* y, const float* r, const float* d, int64_t n, doubl
         out[12] += 1.0;
     }
 }
+
+/* ---- Tensor moments (Results section, first paragraph: inputs of the matrix multiplications are sampled "to
+ * compute the mean, variance, skew and Kurtosis").  The paper does not say which estimators; reading: the plain
+ * population moments about the mean,
+ *     mean = sum x / n,   m_k = sum (x - mean)^k / n  for k = 2, 3, 4,
+ * from which skew = m3 / m2^1.5 and (Pearson) kurtosis = m4 / m2^2 (3 for a normal distribution).
+ * Two passes in binary64, exactly as written.  NaN elements are counted in out[6] and left out of everything
+ * else.  out (8 doubles): n (non-NaN count), mean, m2, m3, m4, max |x|, NaN count, 0. */
+void orc_moments(const float* x, int64_t n, double* out)
+{
+    for (int i = 0; i < 8; ++i) out[i] = 0.0;
+    double cnt = 0.0, sum = 0.0, amax = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (isnan(x[i])) { out[6] += 1.0; continue; }
+        cnt += 1.0;
+        sum += (double)x[i];
+        if (fabs((double)x[i]) > amax) amax = fabs((double)x[i]);
+    }
+    out[0] = cnt; out[5] = amax;
+    if (cnt == 0.0) return;
+    const double mean = sum / cnt;
+    double s2 = 0.0, s3 = 0.0, s4 = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (isnan(x[i])) continue;
+        const double d = (double)x[i] - mean;
+        s2 += d * d;
+        s3 += d * d * d;
+        s4 += d * d * d * d;
+    }
+    out[1] = mean; out[2] = s2 / cnt; out[3] = s3 / cnt; out[4] = s4 / cnt;
+}
