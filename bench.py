@@ -118,6 +118,15 @@ def main():
     for _ in range(args.steps):
         step(("scale", "quantize", "metric"))
     torch.cuda.synchronize()
+    # The tensor-moments pass (not a step of the quantized product: it characterises the operands beforehand) over
+    # the same X and W, timed the same way.
+    events["moments"] = []
+    mom = torch.empty(8, dtype=torch.float64, device=dev)
+    for _ in range(args.steps):
+        for st in state:
+            timed("moments", ("moments",), lambda: (qmm.moments(st["x"], out=mom, workspace=st["ws"]),
+                                                    qmm.moments(st["w"], out=mom, workspace=st["ws"])))
+    torch.cuda.synchronize()
 
     flops = sum(op.flops for op in ops)
     ms_per_step = dt / args.steps * 1e3
@@ -127,7 +136,7 @@ def main():
     per_kind_ms = {k: sum(a.elapsed_time(b) for a, b in v) / args.steps for k, v in events.items()}
     elems_x = sum(op.M * op.K for op in ops); elems_w = sum(op.N * op.K for op in ops); elems_y = sum(op.M * op.N for op in ops)
     algo_bytes = {"scale": 2 * (elems_x + elems_w), "quantize": 3 * (elems_x + elems_w),
-                  "metric": (2 + 4) * elems_y}
+                  "metric": (2 + 4) * elems_y, "moments": 2 * (elems_x + elems_w)}
     gemm_ms_per_launch = per_kind_ms["gemm"] / len(ops)
     gemm_tflops = flops / (per_kind_ms["gemm"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "gemm_kernel (fp8/int8 MFMA, 4 launches per step)",
@@ -163,7 +172,7 @@ def main():
     passes = {k: {"ms_per_step": round(per_kind_ms[k], 4),
                   "GBps": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9, 1),
                   "frac_hbm": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-              for k in ("scale", "quantize", "metric")}
+              for k in ("scale", "quantize", "metric", "moments")}
     nsr = {st["op"].name: float(st["m"][0].item() / st["m"][1].item()) for st in state}
 
     # ---- the oracle timed on the host cores, on a bounded sample of the same workload

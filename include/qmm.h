@@ -185,6 +185,26 @@ qmm_status qmm_metric(const void* y, qmm_dtype y_dtype, const float* y_ref, cons
                       int64_t n, double* out16, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * qmm_moments -- statistics of a tensor the method looks at before choosing a format (Results section, first
+ * paragraph: mean, variance, skew and kurtosis of the matrix-multiply inputs).  Estimators (the paper names none):
+ * population moments about the mean,  mean = sum x / n,  m_k = sum (x - mean)^k / n  for k = 2, 3, 4;
+ * skew = m3 / m2^1.5 and kurtosis = m4 / m2^2 (3 for a normal distribution) are left to the caller.
+ *   x        device, n contiguous elements (bfloat16 or binary32), 16-byte aligned; not modified
+ *   center   finite value the power sums are taken about in the single pass over x (binary64).  0 is right for
+ *            tensors whose mean lies within a few standard deviations of 0; otherwise pass an estimate of the
+ *            mean: the relative error of m_k grows like (1 + ((mean - center) / sigma)^2)^(k/2) * 1e-15.
+ *   out8     device, 8 doubles: n (non-NaN count), mean, m2, m3, m4, max |x|, NaN count, 0.
+ *            NaN elements are counted and otherwise ignored; n = 0 gives zeros.  Infinite elements propagate.
+ *   workspace  device scratch, qmm_moments_workspace_size(n) bytes, 16-byte aligned.
+ * Asynchronous on `stream`; deterministic (fixed order of additions for a given n).
+ * Errors: QMM_ERR_NULL, QMM_ERR_ENUM, QMM_ERR_SHAPE (n < 0 or center not finite), QMM_ERR_ALIGN,
+ * QMM_ERR_WORKSPACE, QMM_ERR_LAUNCH.
+ */
+size_t qmm_moments_workspace_size(int64_t n);
+qmm_status qmm_moments(const void* x, qmm_dtype dtype, int64_t n, double center, double* out8,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * qmm_mfma_rate -- measurement aid, not a step of the method: the rate the matrix units sustain on given operand
  * bytes with no memory traffic, against which the GEMM's rate is read (next to the datasheet peak, which is quoted
  * at the top clock; under matrix load the clock is set by power, and that depends on the operand bytes).

@@ -493,23 +493,26 @@ void orc_metric(const float* y, const float* r, const float* d, int64_t n, doubl
 void orc_moments(const float* x, int64_t n, double* out)
 {
     for (int i = 0; i < 8; ++i) out[i] = 0.0;
-    double cnt = 0.0, sum = 0.0, amax = 0.0;
+    /* sums in the x87 extended format (64-bit significand): the definition is the exact sum, and a sequential
+     * binary64 sum of 10^7 terms already carries a rounding error of 1e-11 relative */
+    long double sum = 0.0L;
+    double cnt = 0.0, amax = 0.0;
     for (int64_t i = 0; i < n; ++i) {
         if (isnan(x[i])) { out[6] += 1.0; continue; }
         cnt += 1.0;
-        sum += (double)x[i];
+        sum += (long double)x[i];
         if (fabs((double)x[i]) > amax) amax = fabs((double)x[i]);
     }
     out[0] = cnt; out[5] = amax;
     if (cnt == 0.0) return;
-    const double mean = sum / cnt;
-    double s2 = 0.0, s3 = 0.0, s4 = 0.0;
+    const long double mean = sum / (long double)cnt;
+    long double s2 = 0.0L, s3 = 0.0L, s4 = 0.0L;
     for (int64_t i = 0; i < n; ++i) {
         if (isnan(x[i])) continue;
-        const double d = (double)x[i] - mean;
+        const long double d = (long double)x[i] - mean;
         s2 += d * d;
         s3 += d * d * d;
         s4 += d * d * d * d;
     }
-    out[1] = mean; out[2] = s2 / cnt; out[3] = s3 / cnt; out[4] = s4 / cnt;
+    out[1] = (double)mean; out[2] = (double)(s2 / cnt); out[3] = (double)(s3 / cnt); out[4] = (double)(s4 / cnt);
 }

@@ -14,7 +14,7 @@ DT_BF16, DT_F32 = 0, 1
 RTNE, STOCHASTIC = 0, 1
 FORMATS = {"int8": INT8, "e4m3": E4M3, "e5m2": E5M2, "bf16": BF16}
 EXPORTS = ["qmm_num_scales", "qmm_scale_workspace_size", "qmm_scale", "qmm_quantize", "qmm_gemm_workspace_size",
-           "qmm_gemm", "qmm_metric_workspace_size", "qmm_metric", "qmm_mfma_rate", "qmm_status_string", "qmm_version"]
+           "qmm_gemm", "qmm_metric_workspace_size", "qmm_metric", "qmm_moments_workspace_size", "qmm_moments", "qmm_mfma_rate", "qmm_status_string", "qmm_version"]
 
 
 class QmmError(RuntimeError):
@@ -59,6 +59,8 @@ def lib():
         L.qmm_gemm.restype = i32; L.qmm_gemm.argtypes = [OP, OP, i64, i64, i64, i64, vp, i32, vp, vp, sz, vp]
         L.qmm_metric_workspace_size.restype = sz; L.qmm_metric_workspace_size.argtypes = [i64]
         L.qmm_metric.restype = i32; L.qmm_metric.argtypes = [vp, i32, vp, vp, i64, vp, vp, sz, vp]
+        L.qmm_moments_workspace_size.restype = sz; L.qmm_moments_workspace_size.argtypes = [i64]
+        L.qmm_moments.restype = i32; L.qmm_moments.argtypes = [vp, i32, i64, ctypes.c_double, vp, vp, sz, vp]
         L.qmm_mfma_rate.restype = i32
         L.qmm_mfma_rate.argtypes = [i32, i32, vp, i64, i64, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.qmm_status_string.restype = ctypes.c_char_p; L.qmm_status_string.argtypes = [i32]
@@ -193,6 +195,23 @@ def metric(y, y_ref, denom=None, out=None, workspace=None):
         workspace = _workspace(L.qmm_metric_workspace_size(n), y.device)
     _check(L.qmm_metric(y.data_ptr(), _dtype_code(y), y_ref.data_ptr(), denom.data_ptr() if denom is not None else None,
                         n, out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()), "qmm_metric")
+    return out
+
+
+MOMENT_FIELDS = ("n", "mean", "m2", "m3", "m4", "absmax", "nan_cnt", "rsv")
+
+
+def moments(x, center=0.0, out=None, workspace=None):
+    """qmm_moments over all elements of the contiguous device tensor x: 8 float64 on the device (MOMENT_FIELDS)."""
+    L = lib()
+    assert x.is_contiguous() and x.is_cuda
+    n = x.numel()
+    if out is None:
+        out = torch.empty(8, dtype=torch.float64, device=x.device)
+    if workspace is None:
+        workspace = _workspace(L.qmm_moments_workspace_size(n), x.device)
+    _check(L.qmm_moments(x.data_ptr(), _dtype_code(x), n, float(center), out.data_ptr(), workspace.data_ptr(),
+                         workspace.numel(), _stream()), "qmm_moments")
     return out
 
 

@@ -67,3 +67,21 @@ def test_argument_errors_are_reported_before_any_launch(L):
     assert L.qmm_metric(fake, 1, fake, None, 8, None, fake, 1 << 20, None) == 1
     assert L.qmm_metric(fake, 1, fake, None, 8, fake, None, 0, None) == 6
     assert L.qmm_metric(fake, 9, fake, None, 8, fake, fake, 1 << 20, None) == 3
+    # split-K shapes need the workspace they ask for
+    assert L.qmm_gemm_workspace_size(ctypes.byref(oa), ctypes.byref(ob), 1, 256, 256, 8192) == 8 * 256 * 256 * 4
+    assert L.qmm_gemm_workspace_size(ctypes.byref(oa), ctypes.byref(ob), 1, 4096, 4096, 8192) == 0
+    assert L.qmm_gemm(ctypes.byref(oa), ctypes.byref(ob), 1, 256, 256, 8192, fake, 1, None, None, 0, None) == 6
+    assert L.qmm_gemm(ctypes.byref(oa), ctypes.byref(ob), 1, 16, 16, (1 << 22) + 16, fake, 1, None, None, 0, None) == 5
+    # moments
+    assert L.qmm_moments_workspace_size(0) >= 56 and L.qmm_moments_workspace_size(1 << 34) <= 1024 * 56
+    assert L.qmm_moments(fake, 0, 8, 0.0, None, fake, 1 << 20, None) == 1
+    assert L.qmm_moments(fake, 5, 8, 0.0, fake, fake, 1 << 20, None) == 3
+    assert L.qmm_moments(fake, 0, -1, 0.0, fake, fake, 1 << 20, None) == 2
+    assert L.qmm_moments(fake, 0, 8, float("nan"), fake, fake, 1 << 20, None) == 2
+    assert L.qmm_moments(fake, 0, 8, float("inf"), fake, fake, 1 << 20, None) == 2
+    assert L.qmm_moments(fake, 0, 8, 0.0, fake, None, 0, None) == 6
+    assert L.qmm_moments(ctypes.c_void_p(0x1004), 0, 8, 0.0, fake, fake, 1 << 20, None) == 4
+    # matrix-rate probe
+    assert L.qmm_mfma_rate(qmm.E4M3, qmm.INT8, fake, 1024, 1, 1, fake, ctypes.byref(ctypes.c_double()), None) == 5
+    assert L.qmm_mfma_rate(qmm.E4M3, qmm.E4M3, None, 1024, 1, 1, fake, ctypes.byref(ctypes.c_double()), None) == 1
+    assert L.qmm_mfma_rate(qmm.E4M3, qmm.E4M3, fake, 8, 1, 1, fake, ctypes.byref(ctypes.c_double()), None) == 2
