@@ -12,7 +12,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kMaxFlatBlocks = 1024;   // 4 workgroups per CU on 256 CUs; 4 partials per thread in the fold
-constexpr int kColSlabRows = 256;      // rows folded by one workgroup in the column-group kernel
+constexpr int kColSlabRows = 128;      // rows folded by one workgroup in the column-group kernel
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -109,7 +109,16 @@ absmax_cols_bf16(const uint16_t* __restrict__ x, int64_t batch_stride, int64_t r
     u16x2 m[4] = {};
     if (vcol * 8 < cols) {
         const uint16_t* base = x + (int64_t)blockIdx.z * batch_stride + vcol * 8;
-        for (int64_t r = r0 + rl; r < r1; r += 8)
+        int64_t r = r0 + rl;
+        // four rows per trip: the loads are in flight together
+        for (; r + 24 < r1; r += 32) {
+            const u32x4 a = *reinterpret_cast<const u32x4*>(base + r * row_stride);
+            const u32x4 b = *reinterpret_cast<const u32x4*>(base + (r + 8) * row_stride);
+            const u32x4 c = *reinterpret_cast<const u32x4*>(base + (r + 16) * row_stride);
+            const u32x4 d = *reinterpret_cast<const u32x4*>(base + (r + 24) * row_stride);
+            fold_bf16x8(a, m); fold_bf16x8(b, m); fold_bf16x8(c, m); fold_bf16x8(d, m);
+        }
+        for (; r < r1; r += 8)
             fold_bf16x8(*reinterpret_cast<const u32x4*>(base + r * row_stride), m);
     }
 #pragma unroll
@@ -166,17 +175,34 @@ finalize_single(const uint32_t* __restrict__ partial, int64_t batch, int64_t P, 
     m = block_max_u32(m);
     if (threadIdx.x == 0) delta[g] = delta_from_absmax_bits(m, qmax);
 }
+// Workgroup = 32 channels x 8 lanes over the (matrix, partial) pairs of the group; max is order-free.
 __global__ void __launch_bounds__(kThreads)
 finalize_channels(const uint32_t* __restrict__ partial, int64_t batch, int64_t P, int64_t C, int64_t G, float qmax,
                   float* __restrict__ delta)
 {
-    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    __shared__ uint32_t s[8][32];
+    const int cl = threadIdx.x & 31, pl = threadIdx.x >> 5;
+    const int64_t c = (int64_t)blockIdx.x * 32 + cl;
     const int64_t g = blockIdx.y;
-    if (c >= C) return;
     uint32_t m = 0;
-    for (int64_t b = g; b < batch; b += G)
-        for (int64_t p = 0; p < P; ++p) m = max(m, partial[(b * P + p) * C + c]);
-    delta[g * C + c] = delta_from_absmax_bits(m, qmax);
+    if (c < C) {
+        for (int64_t b = g; b < batch; b += G) {
+            const uint32_t* base = partial + b * P * C + c;
+            int64_t p = pl;
+            for (; p + 24 < P; p += 32) {      // four loads in flight
+                const uint32_t v0 = base[p * C], v1 = base[(p + 8) * C], v2 = base[(p + 16) * C], v3 = base[(p + 24) * C];
+                m = max(m, max(max(v0, v1), max(v2, v3)));
+            }
+            for (; p < P; p += 8) m = max(m, base[p * C]);
+        }
+    }
+    s[pl][cl] = m;
+    __syncthreads();
+    if (pl == 0 && c < C) {
+#pragma unroll
+        for (int k = 1; k < 8; ++k) m = max(m, s[k][cl]);
+        delta[g * C + c] = delta_from_absmax_bits(m, qmax);
+    }
 }
 
 struct Plan {
@@ -318,7 +344,7 @@ extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_g
     if (C == 1)
         finalize_single<<<(unsigned)G, kThreads, 0, s>>>(partial, fold_batch, P, G, qmax, delta_out);
     else
-        finalize_channels<<<dim3((unsigned)((C + kThreads - 1) / kThreads), (unsigned)G), kThreads, 0, s>>>(
+        finalize_channels<<<dim3((unsigned)((C + 31) / 32), (unsigned)G), kThreads, 0, s>>>(
             partial, fold_batch, P, C, G, qmax, delta_out);
     return launch_status();
 }
