@@ -68,6 +68,8 @@ def lib():
         L.orc_ref_gemm.argtypes = [vp, vp, i64, i64, i64, i64, vp]
         L.orc_metric.restype = None
         L.orc_metric.argtypes = [vp, vp, vp, i64, vp]
+        L.orc_dequantize_codes.restype = None
+        L.orc_dequantize_codes.argtypes = [vp, i64, i64, i64, i32, i32, i64, vp, vp]
         L.orc_moments.restype = None
         L.orc_moments.argtypes = [vp, i64, vp]
         _lib = L
@@ -236,6 +238,20 @@ def metric(y, r, d=None):
     out = np.empty(16, dtype=np.float64)
     lib().orc_metric(_p(y), _p(r), _p(d) if d is not None else None, y.size, _p(out))
     return out
+
+
+def dequantize_codes(codes, fmt, delta, per_channel=False, batch_groups=1):
+    """Values (float32) of codes [batch, nc, kc] (or [nc, kc]) as laid out by quantize: code value times step size."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    shape = codes.shape
+    if codes.ndim == 2:
+        codes = codes[None]
+    b, nc, kc = codes.shape
+    delta = np.ascontiguousarray(delta, dtype=np.float32)
+    assert delta.size == batch_groups * (nc if per_channel else 1)
+    out = np.empty(codes.shape, dtype=np.float32)
+    lib().orc_dequantize_codes(_p(codes), b, nc, kc, fmt, int(per_channel), batch_groups, _p(delta), _p(out))
+    return out.reshape(shape)
 
 
 MOMENT_FIELDS = ("n", "mean", "m2", "m3", "m4", "absmax", "nan_cnt", "rsv")

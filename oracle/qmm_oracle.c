@@ -516,3 +516,22 @@ void orc_moments(const float* x, int64_t n, double* out)
     }
     out[1] = (double)mean; out[2] = (double)(s2 / cnt); out[3] = (double)(s3 / cnt); out[4] = (double)(s4 / cnt);
 }
+
+/* ---- The reduced-precision value of a quantized element (the v-tilde of Eq. 2): the value of its code times the
+ * step size of its scale group, one binary32 multiply (the code's value is exact in binary32).  Layout of codes
+ * and indexing of delta as written by orc_quantize: codes [batch][nc][kc] with the contracting axis last,
+ * delta[(b % groups) * C + (per_channel ? row : 0)].  An FP8 NaN code gives NaN; the INT8 code 0x80, which the
+ * encoder never produces, gives -128 delta. */
+void orc_dequantize_codes(const uint8_t* codes, int64_t batch, int64_t nc, int64_t kc, int fmt,
+                          int per_channel, int64_t groups, const float* delta, float* out)
+{
+    const int64_t C = per_channel ? nc : 1;
+    for (int64_t b = 0; b < batch; ++b)
+        for (int64_t r = 0; r < nc; ++r) {
+            const float d = delta[(b % groups) * C + (per_channel ? r : 0)];
+            for (int64_t k = 0; k < kc; ++k) {
+                const int64_t i = (b * nc + r) * kc + k;
+                out[i] = (float)orc_code_value(fmt, codes[i]) * d;
+            }
+        }
+}
