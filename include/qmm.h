@@ -185,6 +185,20 @@ qmm_status qmm_metric(const void* y, qmm_dtype y_dtype, const float* y_ref, cons
                       int64_t n, double* out16, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * qmm_dequantize -- the reduced-precision value of every quantized element (the v-tilde of Eq. 2), for looking at
+ * the quantization error of a tensor itself rather than of a product:
+ *     out[b][r][k] = fl32( value(codes[b][r][k]) * delta[(b % batch_groups) * C + (per_channel ? r : 0)] )
+ * with codes and delta exactly as qmm_quantize takes / writes them (C = rows if per_channel, else 1); the code's
+ * value is exact in binary32, so this is one rounding; bfloat16 output rounds that once more (RNE).
+ * An FP8 NaN code gives NaN, an E5M2 infinity code gives infinity, the INT8 code 0x80 gives -128 delta.
+ *   codes  device [batch][rows][K] uint8;  out  device [batch][rows][K] of out_dtype; caller-owned.
+ * Asynchronous on `stream`, uses no workspace.  Empty tensors return QMM_OK.
+ * Errors: QMM_ERR_NULL, QMM_ERR_ENUM, QMM_ERR_SHAPE, QMM_ERR_ALIGN (out not aligned to its element), QMM_ERR_LAUNCH.
+ */
+qmm_status qmm_dequantize(const uint8_t* codes, int64_t batch, int64_t rows, int64_t K, qmm_format fmt,
+                          const qmm_granularity* g, const float* delta, void* out, qmm_dtype out_dtype, void* stream);
+
+/*
  * qmm_moments -- statistics of a tensor the method looks at before choosing a format (Results section, first
  * paragraph: mean, variance, skew and kurtosis of the matrix-multiply inputs).  Estimators (the paper names none):
  * population moments about the mean,  mean = sum x / n,  m_k = sum (x - mean)^k / n  for k = 2, 3, 4;

@@ -30,6 +30,19 @@ def backward_error_sweep(dofs=W.BACKWARD_ERROR_DOFS, formats=(qmm.INT8, qmm.E4M3
     return [backward_error_row(d, f, n, device) for d in dofs for f in formats]
 
 
+def relative_error_profile(fmt, points=4096, decades=11.0, device="cuda:0"):
+    """Relative error of Eq. 2 over magnitudes (the figure comparing the three formats under RTNE): `points`
+    positive bfloat16 magnitudes log-spaced over `decades` decades below the largest one, 1.0, which the step size
+    maps onto the format's largest code.  Returns (magnitudes, relative errors) as float32 CPU tensors; a value
+    quantized to zero has relative error 1."""
+    x = torch.logspace(-decades, 0.0, points, dtype=torch.float32).to(torch.bfloat16).to(device).reshape(1, -1)
+    delta = qmm.scale(x, 1, fmt)
+    codes = qmm.quantize(x, 1, fmt, delta)
+    v = qmm.dequantize(codes, fmt, delta)
+    xf = x.float()
+    return xf.reshape(-1).cpu(), ((v.reshape(1, -1) - xf).abs() / xf).reshape(-1).cpu()
+
+
 def main():
     names = {v: k for k, v in qmm.FORMATS.items()}
     rows = backward_error_sweep()
@@ -37,6 +50,13 @@ def main():
     for r in rows:
         dof = "normal" if r["dof"] is None else str(r["dof"])
         print(f"{dof:>6s} {names[r['format']]:>6s} {r['be_max']:11.3e} {r['be_mean']:11.3e} {r['nsr']:11.3e}")
+    print("\nworst relative error of a value (Eq. 2) per decade of magnitude below the tensor's largest one")
+    print(f"{'decade':>10s} " + " ".join(f"{n:>10s}" for n in ("int8", "e4m3", "e5m2")))
+    prof = {f: relative_error_profile(f) for f in (qmm.INT8, qmm.E4M3, qmm.E5M2)}
+    x = prof[qmm.INT8][0]
+    for d in range(0, 11):
+        sel = (x <= 10.0 ** -d) & (x > 10.0 ** -(d + 1))
+        print(f"  1e-{d + 1:<2d}..1e-{d:<2d}" + " ".join(f"{float(prof[f][1][sel].max()):10.3e}" for f in (qmm.INT8, qmm.E4M3, qmm.E5M2)))
 
 
 if __name__ == "__main__":

@@ -14,7 +14,7 @@ DT_BF16, DT_F32 = 0, 1
 RTNE, STOCHASTIC = 0, 1
 FORMATS = {"int8": INT8, "e4m3": E4M3, "e5m2": E5M2, "bf16": BF16}
 EXPORTS = ["qmm_num_scales", "qmm_scale_workspace_size", "qmm_scale", "qmm_quantize", "qmm_gemm_workspace_size",
-           "qmm_gemm", "qmm_metric_workspace_size", "qmm_metric", "qmm_moments_workspace_size", "qmm_moments", "qmm_mfma_rate", "qmm_status_string", "qmm_version"]
+           "qmm_gemm", "qmm_metric_workspace_size", "qmm_metric", "qmm_dequantize", "qmm_moments_workspace_size", "qmm_moments", "qmm_mfma_rate", "qmm_status_string", "qmm_version"]
 
 
 class QmmError(RuntimeError):
@@ -59,6 +59,7 @@ def lib():
         L.qmm_gemm.restype = i32; L.qmm_gemm.argtypes = [OP, OP, i64, i64, i64, i64, vp, i32, vp, vp, sz, vp]
         L.qmm_metric_workspace_size.restype = sz; L.qmm_metric_workspace_size.argtypes = [i64]
         L.qmm_metric.restype = i32; L.qmm_metric.argtypes = [vp, i32, vp, vp, i64, vp, vp, sz, vp]
+        L.qmm_dequantize.restype = i32; L.qmm_dequantize.argtypes = [vp, i64, i64, i64, i32, GP, vp, vp, i32, vp]
         L.qmm_moments_workspace_size.restype = sz; L.qmm_moments_workspace_size.argtypes = [i64]
         L.qmm_moments.restype = i32; L.qmm_moments.argtypes = [vp, i32, i64, ctypes.c_double, vp, vp, sz, vp]
         L.qmm_mfma_rate.restype = i32
@@ -195,6 +196,21 @@ def metric(y, y_ref, denom=None, out=None, workspace=None):
         workspace = _workspace(L.qmm_metric_workspace_size(n), y.device)
     _check(L.qmm_metric(y.data_ptr(), _dtype_code(y), y_ref.data_ptr(), denom.data_ptr() if denom is not None else None,
                         n, out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()), "qmm_metric")
+    return out
+
+
+def dequantize(codes, fmt, delta, per_channel=False, batch_groups=1, out_dtype=torch.float32, out=None):
+    """qmm_dequantize: values of the uint8 device tensor codes [batch, rows, K] (or [rows, K])."""
+    L = lib()
+    assert codes.dtype == torch.uint8 and codes.is_contiguous() and codes.is_cuda
+    c3 = codes if codes.dim() == 3 else codes.unsqueeze(0)
+    b, r, k = c3.shape
+    g = granularity(per_channel, batch_groups)
+    assert delta.dtype == torch.float32 and delta.numel() == batch_groups * (r if per_channel else 1)
+    if out is None:
+        out = torch.empty(codes.shape, dtype=out_dtype, device=codes.device)
+    _check(L.qmm_dequantize(codes.data_ptr(), b, r, k, fmt, ctypes.byref(g), delta.data_ptr(), out.data_ptr(),
+                            _dtype_code(out), _stream()), "qmm_dequantize")
     return out
 
 

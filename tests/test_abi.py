@@ -85,3 +85,10 @@ def test_argument_errors_are_reported_before_any_launch(L):
     assert L.qmm_mfma_rate(qmm.E4M3, qmm.INT8, fake, 1024, 1, 1, fake, ctypes.byref(ctypes.c_double()), None) == 5
     assert L.qmm_mfma_rate(qmm.E4M3, qmm.E4M3, None, 1024, 1, 1, fake, ctypes.byref(ctypes.c_double()), None) == 1
     assert L.qmm_mfma_rate(qmm.E4M3, qmm.E4M3, fake, 8, 1, 1, fake, ctypes.byref(ctypes.c_double()), None) == 2
+    # dequantize
+    assert L.qmm_dequantize(fake, 1, 4, 16, qmm.E4M3, ctypes.byref(g), fake, None, 1, None) == 1
+    assert L.qmm_dequantize(fake, 1, 4, 16, 9, ctypes.byref(g), fake, fake, 1, None) == 3
+    assert L.qmm_dequantize(fake, 1, -4, 16, qmm.E4M3, ctypes.byref(g), fake, fake, 1, None) == 2
+    assert L.qmm_dequantize(None, 1, 4, 16, qmm.E4M3, ctypes.byref(g), fake, fake, 1, None) == 1
+    assert L.qmm_dequantize(fake, 1, 4, 16, qmm.E4M3, ctypes.byref(g), fake, ctypes.c_void_p(0x1002), 1, None) == 4
+    assert L.qmm_dequantize(None, 0, 4, 16, qmm.E4M3, ctypes.byref(g), None, fake, 1, None) == 0
