@@ -129,27 +129,29 @@ gemm_kernel(GemmArgs g)
     const int wm = wave / NWN, wn = wave % NWN;
 
     // ---- workgroup id -> (batch, tile_m, tile_n), XCD-aware and grouped along m
-    const int64_t tiles_per_batch = (int64_t)g.tiles_m * g.tiles_n;
-    const int64_t total_tiles = tiles_per_batch * g.batch;
-    const int64_t total = total_tiles * g.splits;
-    int64_t pid = blockIdx.x;
+    // (all in 32-bit unsigned arithmetic: the host rejects launches of 2^31 workgroups or more, and 64-bit
+    // divisions cost a few hundred instructions each, which counts when a workgroup's own work is small)
+    const uint32_t tiles_per_batch = (uint32_t)g.tiles_m * (uint32_t)g.tiles_n;
+    const uint32_t total_tiles = tiles_per_batch * (uint32_t)g.batch;
+    const uint32_t total = total_tiles * (uint32_t)g.splits;
+    uint32_t pid = blockIdx.x;
     {
-        const int64_t per = (total + kNumXcd - 1) / kNumXcd, tall = total % kNumXcd;
-        const int64_t xcd = pid % kNumXcd, loc = pid / kNumXcd;
+        const uint32_t per = (total + kNumXcd - 1) / kNumXcd, tall = total % kNumXcd;
+        const uint32_t xcd = pid % kNumXcd, loc = pid / kNumXcd;
         pid = (tall == 0 || xcd < tall) ? xcd * per + loc : tall * per + (xcd - tall) * (per - 1) + loc;
     }
     // the divisions run on the vector unit; their results are the same in every lane and are moved to scalar
     // registers, so that everything derived from them (tile base addresses above all) is scalar as well
     // split-K: consecutive workgroups (same XCD) work on neighbouring tiles of the same K range
     const int split = __builtin_amdgcn_readfirstlane((int)(pid / total_tiles));
-    pid -= split * total_tiles;
+    pid -= (uint32_t)split * total_tiles;
     const int64_t bidx = __builtin_amdgcn_readfirstlane((int)(pid / tiles_per_batch));
-    const int64_t t = pid - bidx * tiles_per_batch;
-    constexpr int GROUP_M = 8;
-    const int64_t in_group = (int64_t)GROUP_M * g.tiles_n;
-    const int64_t grp = t / in_group;
-    const int64_t first_m = grp * GROUP_M;
-    const int64_t gsz = min((int64_t)GROUP_M, g.tiles_m - first_m);
+    const uint32_t t = pid - (uint32_t)bidx * tiles_per_batch;
+    constexpr uint32_t GROUP_M = 8;
+    const uint32_t in_group = GROUP_M * (uint32_t)g.tiles_n;
+    const uint32_t grp = t / in_group;
+    const uint32_t first_m = grp * GROUP_M;
+    const uint32_t gsz = min(GROUP_M, (uint32_t)g.tiles_m - first_m);
     const int64_t tile_m = __builtin_amdgcn_readfirstlane((int)(first_m + (t - grp * in_group) % gsz));
     const int64_t tile_n = __builtin_amdgcn_readfirstlane((int)((t - grp * in_group) / gsz));
     const int64_t m0 = tile_m * BM, n0 = tile_n * BN;
