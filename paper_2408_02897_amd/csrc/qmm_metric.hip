@@ -130,17 +130,19 @@ metric_partial(const void* __restrict__ yv, const float* __restrict__ r, const f
 {
     Acc acc;
     const int64_t nvec = n >> 2;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
     const int64_t tid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const f32x4* r4 = reinterpret_cast<const f32x4*>(r);
     const f32x4* d4 = reinterpret_cast<const f32x4*>(d);
-    int64_t i = tid;
-    // two vectors of four elements per trip: both loads are in flight before the arithmetic of either starts
-    for (; i + stride < nvec; i += 2 * stride) {
-        const f32x4 y0 = load_y4<Y_BF16>(yv, i), y1 = load_y4<Y_BF16>(yv, i + stride);
-        const f32x4 r0 = r4[i], r1 = r4[i + stride];
+    // A workgroup takes two consecutive pieces of 256 vectors per trip and the grid sweeps the arrays front to
+    // back, so the loads in flight are neighbours in memory (loads a whole grid stride apart read large arrays
+    // up to 25 % slower).  Both loads are in flight before the arithmetic of either starts.
+    const int64_t stride = (int64_t)gridDim.x * kThreads * 2;
+    int64_t i = (int64_t)blockIdx.x * kThreads * 2 + threadIdx.x;
+    for (; i + kThreads < nvec; i += stride) {
+        const f32x4 y0 = load_y4<Y_BF16>(yv, i), y1 = load_y4<Y_BF16>(yv, i + kThreads);
+        const f32x4 r0 = r4[i], r1 = r4[i + kThreads];
         f32x4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (HAS_D) { d0 = d4[i]; d1 = d4[i + stride]; }
+        if constexpr (HAS_D) { d0 = d4[i]; d1 = d4[i + kThreads]; }
         bool sp = false;
 #pragma unroll
         for (int j = 0; j < 4; ++j) sp = sp || Acc::special<HAS_D>(y0[j], r0[j], d0[j]) || Acc::special<HAS_D>(y1[j], r1[j], d1[j]);
@@ -157,7 +159,7 @@ metric_partial(const void* __restrict__ yv, const float* __restrict__ r, const f
             for (int j = 0; j < 4; ++j) acc.add<HAS_D>(y1[j], r1[j], d1[j]);
         }
     }
-    if (i < nvec) {
+    if (i < nvec) {      // ragged end: the first piece of a workgroup's last trip
         const f32x4 y0 = load_y4<Y_BF16>(yv, i);
         const f32x4 r0 = r4[i];
         f32x4 d0 = {0.f, 0.f, 0.f, 0.f};

@@ -52,7 +52,6 @@ moments_partial(const void* __restrict__ x, int64_t n, double center, double* __
 {
     Sums acc;
     const int64_t nvec = n >> 3;                       // vectors of eight elements
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
     const int64_t tid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     auto consume = [&](const float (&e)[8]) {
         bool any_nan = false;
@@ -67,17 +66,23 @@ moments_partial(const void* __restrict__ x, int64_t n, double center, double* __
             for (int i = 0; i < 8; ++i) acc.add(e[i], center);
         }
     };
-    int64_t vi = tid;
-    // four vectors per trip: all four loads are in flight before the arithmetic of the first starts
-    for (; vi + 3 * stride < nvec; vi += 4 * stride) {
+    // Four consecutive pieces of 256 vectors per workgroup and trip, the grid sweeping the tensor front to back:
+    // a thread's four loads in flight are neighbours in memory (a whole grid stride apart they read a large
+    // tensor up to 25 % slower); all four are in flight before the arithmetic of the first starts.
+    const int64_t sweep = (int64_t)gridDim.x * kThreads * 4;
+    int64_t vi = (int64_t)blockIdx.x * kThreads * 4 + threadIdx.x;
+    for (; vi + 3 * kThreads < nvec; vi += sweep) {
         float e0[8], e1[8], e2[8], e3[8];
-        load8<BF16>(x, vi, e0); load8<BF16>(x, vi + stride, e1); load8<BF16>(x, vi + 2 * stride, e2); load8<BF16>(x, vi + 3 * stride, e3);
+        load8<BF16>(x, vi, e0); load8<BF16>(x, vi + kThreads, e1); load8<BF16>(x, vi + 2 * kThreads, e2); load8<BF16>(x, vi + 3 * kThreads, e3);
         consume(e0); consume(e1); consume(e2); consume(e3);
     }
-    for (; vi < nvec; vi += stride) {
-        float e[8];
-        load8<BF16>(x, vi, e);
-        consume(e);
+    if (vi < nvec) {     // ragged end: at most three pieces of one workgroup
+        for (int u = 0; u < 4; ++u)
+            if (vi + u * kThreads < nvec) {
+                float e[8];
+                load8<BF16>(x, vi + u * kThreads, e);
+                consume(e);
+            }
     }
     const int64_t t = (nvec << 3) + tid;               // tail elements (n % 8), one thread each
     if (t < n) {

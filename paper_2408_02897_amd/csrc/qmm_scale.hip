@@ -52,14 +52,21 @@ absmax_flat_bf16(const uint16_t* __restrict__ x, int64_t batch_stride, int64_t n
 {
     const u32x4* p = reinterpret_cast<const u32x4*>(x + (int64_t)blockIdx.y * batch_stride);
     u16x2 m[4] = {};
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    for (; i + 3 * stride < nvec; i += 4 * stride) {
-        const u32x4 a = p[i], b = p[i + stride];
-        const u32x4 c = p[i + 2 * stride], d = p[i + 3 * stride];
+    // A workgroup takes four consecutive 4 KB pieces per trip and the grid sweeps the tensor front to back: the
+    // four loads a thread has in flight are then neighbours in memory.  (With the loads a whole grid stride apart
+    // the same kernel reads a large tensor up to 25 % slower: four distant streams per thread.)
+    const int64_t stride = (int64_t)gridDim.x * kThreads * 4;
+    int64_t i = (int64_t)blockIdx.x * kThreads * 4 + threadIdx.x;
+    for (; i + 3 * kThreads < nvec; i += stride) {
+        const u32x4 a = p[i], b = p[i + kThreads];
+        const u32x4 c = p[i + 2 * kThreads], d = p[i + 3 * kThreads];
         fold_bf16x8(a, m); fold_bf16x8(b, m); fold_bf16x8(c, m); fold_bf16x8(d, m);
     }
-    for (; i < nvec; i += stride) fold_bf16x8(p[i], m);
+    // the ragged end: at most three pieces of one workgroup
+    if (i < nvec) {
+        for (int u = 0; u < 4; ++u)
+            if (i + u * kThreads < nvec) fold_bf16x8(p[i + u * kThreads], m);
+    }
     const uint32_t r = block_max_u32(finish_bf16(m));
     if (threadIdx.x == 0) partial[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = r;
 }
