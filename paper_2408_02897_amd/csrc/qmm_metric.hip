@@ -15,6 +15,23 @@ constexpr int kMaxBlocks = 2048;   // 8 workgroups per CU; also 8 partials per t
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
+// n / d for finite n >= 0 and finite d > 0 that were converted from binary32 (exponents within +-150 or so, differences
+// of two such values included).  This is the usual reciprocal-refinement division -- hardware reciprocal estimate,
+// two Newton steps on it, the quotient, one residual correction -- i.e. what the compiler emits for `/` on binary64
+// without the operand pre-scaling and the special-case fix-up around it, neither of which can trigger in this
+// exponent range: the bits are those of the IEEE quotient, for 8 instructions instead of 11.  (The metric pass is
+// as much ALU- as HBM-bound; this division is its largest single cost.)
+QMM_DEV double quotient_plain(double n, double d)
+{
+    const double x0 = __builtin_amdgcn_rcp(d);
+    const double e0 = fma(-d, x0, 1.0);
+    const double x1 = fma(x0, e0, x0);
+    const double e1 = fma(-d, x1, 1.0);
+    const double x2 = fma(x1, e1, x1);
+    const double q0 = n * x2;
+    return fma(fma(-d, q0, n), x2, q0);
+}
+
 // Running sums of one thread.  Branch-free: an element whose error is NaN contributes zeros and bumps nan_cnt.
 struct Acc {
     double s_ee = 0, s_rr = 0, s_ae = 0, s_ar = 0, m_e = 0, m_r = 0;
@@ -33,11 +50,11 @@ struct Acc {
         s_ar += ar;
         m_e = fmax(m_e, ae);
         m_r = fmax(m_r, ar);
-        const double q = ae / ar;
+        const double q = quotient_plain(ae, ar);
         re_sum += q;
         re_max = fmax(re_max, q);
         if constexpr (HAS_D) {
-            const double qb = ae / (double)df;
+            const double qb = quotient_plain(ae, (double)df);
             be_sum += qb;
             be_max = fmax(be_max, qb);
         }
@@ -51,9 +68,11 @@ struct Acc {
     // true if add_plain() would not give add()'s result for this element
     template <bool HAS_D> static QMM_DEV bool special(float yf, float rf, float df)
     {
-        const float e = yf - rf;                    // NaN exactly when the binary64 difference is NaN
-        bool sp = !(e == e) || rf == 0.0f;
-        if constexpr (HAS_D) sp = sp || !(df > 0.0f);
+        // e is NaN exactly when the binary64 difference is NaN; an infinite e (an infinite input, or a difference
+        // that overflows binary32 only) also takes the general path, which divides with the full IEEE sequence
+        const float e = yf - rf;
+        bool sp = !(fabsf(e) < __builtin_inff()) || rf == 0.0f;
+        if constexpr (HAS_D) sp = sp || !(df > 0.0f && df < __builtin_inff());
         return sp;
     }
 

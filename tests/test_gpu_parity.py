@@ -331,6 +331,29 @@ def test_metric_parity(n, y_bf16, with_d):
         assert abs(got[i] - want[i]) <= 1e-10 * abs(want[i]), (i, got[i], want[i])
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_metric_quotients_exact_over_the_binary32_range(seed):
+    """Eq. 2 / Eq. 3 quotients of ordinary elements are IEEE binary64 quotients whatever the magnitudes: references
+    and denominators log-uniform over the whole binary32 range, subnormals included, with no zero, NaN or infinity
+    anywhere (so every wavefront takes the path with the short division); the maxima must equal the oracle's."""
+    rng = np.random.default_rng(100 + seed)
+    n = 8192 + 4 * seed
+    def wide(lo, hi):
+        return (np.exp2(rng.uniform(lo, hi, n)) * (1.0 + rng.random(n)) * rng.choice([-1.0, 1.0], n)).astype(np.float32)
+    r = wide(-148, 126)
+    y = (r.astype(np.float64) * (1.0 + rng.uniform(-0.5, 0.5, n))).astype(np.float32)
+    k = rng.integers(0, n, 64)
+    y[k] = wide(-148, 126)[k]                     # unrelated magnitudes: quotients from 2^-270 to 2^270
+    d = np.abs(wide(-148, 126))
+    assert np.all(r != 0) and np.all(d > 0) and np.all(np.isfinite(y.astype(np.float64) - r))
+    want = O.metric(y, r, d)
+    got = qmm.metric(torch.from_numpy(y).to(DEV), torch.from_numpy(r).to(DEV), torch.from_numpy(d).to(DEV)).cpu().numpy()
+    for i in (4, 5, 7, 8, 10, 11, 12, 13):
+        assert got[i] == want[i], (i, got[i], want[i])
+    for i in (0, 1, 2, 3, 6, 9):
+        assert abs(got[i] - want[i]) <= 1e-10 * abs(want[i]), (i, got[i], want[i])
+
+
 # ----------------------------------------------------------- the whole path
 @pytest.mark.parametrize("fmt", FMTS)
 @pytest.mark.parametrize("per_channel", [False, True])
