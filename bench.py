@@ -144,6 +144,9 @@ def main():
                 "frac": round(gemm_tflops / PEAK[args.format], 4),
                 "traffic": GEMM_TRAFFIC.get((args.workload, args.format)),
                 "avg_launch_ms": round(gemm_ms_per_launch, 4)}
+    g_ms = [a.elapsed_time(b) for a, b in events["gemm"]]       # launch order: step-major, op-minor
+    roofline["median_launch_ms_by_op"] = {st["op"].name: round(sorted(g_ms[i::len(ops)])[args.steps // 2], 4)
+                                          for i, st in enumerate(state)}
     # ---- what the matrix units sustain on these very codes with no memory traffic (and on constant codes): the
     #      chip's clock under matrix load is set by power, which depends on the operand bytes
     n_cu = torch.cuda.get_device_properties(0).multi_processor_count
@@ -169,6 +172,31 @@ def main():
     roofline["event_pair_around_one_element_kernel_ms"] = round(sorted(ov)[len(ov) // 2], 4)
     roofline["mfma_only_tflops"] = {"workload_codes": round(mfma_codes, 1), "constant_codes": round(mfma_const, 1)}
     roofline["frac_of_mfma_only_on_workload_codes"] = round(gemm_tflops / mfma_codes, 4)
+    # ---- context only, no part of the path: the vendor library's FP8 GEMM (torch._scaled_mm, i.e. hipBLASLt) on this
+    #      step's own code matrices with unit scales and bf16 output, event pairs around single launches as above
+    def library_context():
+        if fmt == qmm.INT8:
+            return None
+        try:
+            dt8 = torch.float8_e4m3fn if fmt == qmm.E4M3 else torch.float8_e5m2
+            one = torch.ones((), device=dev)
+            total_ms, per_op = 0.0, {}
+            for st in state:
+                a, b = st["cx"][0].view(dt8), st["cw"][0].view(dt8)
+                ts = []
+                for it in range(13):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(); torch._scaled_mm(a, b.t(), scale_a=one, scale_b=one, out_dtype=torch.bfloat16); e1.record()
+                    torch.cuda.synchronize()
+                    if it >= 3:
+                        ts.append(e0.elapsed_time(e1))
+                per_op[st["op"].name] = round(sorted(ts)[len(ts) // 2], 4)
+                total_ms += per_op[st["op"].name]
+            return {"what": "torch._scaled_mm (hipBLASLt) on the same codes, median of 10 single launches per op",
+                    "tflops": round(flops / (total_ms * 1e-3) / 1e12, 1), "ms_per_launch": per_op}
+        except Exception as e:          # the library may lack the call: the context line is then left out
+            return {"error": str(e)[:120]}
+    roofline["vendor_library_gemm"] = library_context()
     passes = {k: {"ms_per_step": round(per_kind_ms[k], 4),
                   "GBps": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9, 1),
                   "frac_hbm": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
