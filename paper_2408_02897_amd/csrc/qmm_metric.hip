@@ -172,10 +172,13 @@ metric_partial(const void* __restrict__ yv, const float* __restrict__ r, const f
             for (int j = 0; j < 4; ++j) acc.add_plain<HAS_D>(y1[j], r1[j], d1[j]);
             acc.count_plain<HAS_D>(8u);
         } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc.add<HAS_D>(y0[j], r0[j], d0[j]);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc.add<HAS_D>(y1[j], r1[j], d1[j]);
+            // rare path, kept rolled: unrolled, its eight interleaved IEEE divisions set the kernel's register
+            // count (99 instead of 72) and with it the number of resident wavefronts
+#pragma unroll 1
+            for (int j = 0; j < 8; ++j) {
+                const f32x4 yy = j < 4 ? y0 : y1, rr = j < 4 ? r0 : r1, dd = j < 4 ? d0 : d1;
+                acc.add<HAS_D>(yy[j & 3], rr[j & 3], dd[j & 3]);
+            }
         }
     }
     if (i < nvec) {      // ragged end: the first piece of a workgroup's last trip

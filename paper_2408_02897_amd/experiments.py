@@ -43,6 +43,46 @@ def relative_error_profile(fmt, points=4096, decades=11.0, device="cuda:0"):
     return xf.reshape(-1).cpu(), ((v.reshape(1, -1) - xf).abs() / xf).reshape(-1).cpu()
 
 
+# Candidates of the per-op choice, cheapest scaling first: one step size per tensor before one per channel.  The
+# three 8-bit formats cost the same matrix rate on this part, so within a granularity the order is by typical error
+# on near-normal operands (E4M3, INT8, E5M2).
+CANDIDATES = ((qmm.E4M3, False), (qmm.INT8, False), (qmm.E5M2, False),
+              (qmm.E4M3, True), (qmm.INT8, True), (qmm.E5M2, True))
+
+
+def op_error(x, w, fmt_x, fmt_w, per_channel, ref=None):
+    """Quantized product X W^T of one op (x: [M, K], w: [N, K], device bfloat16) against the high-precision product:
+    dict with the noise-to-signal ratio and the mean / max relative error of Eq. 2.  Library calls only."""
+    (cx, ox), _ = qmm.quantized_operand(x, 1, fmt_x, per_channel=per_channel)
+    (cw, ow), _ = qmm.quantized_operand(w, 1, fmt_w, per_channel=per_channel)
+    y = qmm.gemm((cx, ox), (cw, ow), torch.float32)
+    if ref is None:
+        ref = qmm.reference_gemm(x.unsqueeze(0), w.unsqueeze(0))
+    f = dict(zip(qmm.METRIC_FIELDS, qmm.metric(y, ref).cpu().tolist()))
+    return {"nsr": f["S_ee"] / f["S_rr"] if f["S_rr"] > 0 else float("inf"),
+            "re_mean": f["RE_sum"] / max(f["RE_cnt"], 1.0), "re_max": f["RE_max"], "fields": f}
+
+
+def format_sweep(x, w, candidates=CANDIDATES):
+    """Error of every candidate (format, per_channel) on one op; the same format on both operands."""
+    ref = qmm.reference_gemm(x.unsqueeze(0), w.unsqueeze(0))
+    return [dict(format=fmt, per_channel=pc, **op_error(x, w, fmt, fmt, pc, ref)) for fmt, pc in candidates]
+
+
+def choose_format(x, w, nsr_max, candidates=CANDIDATES):
+    """The error metric applied to the mapping of one op onto a format (the mapping the Conclusion calls the crucial
+    step; an extension: the paper chooses by training runs, not per op): the first candidate, in the order given,
+    whose noise-to-signal ratio against the high-precision product is at most `nsr_max`; None if there is none (the
+    op stays in bfloat16).  Returns (choice or None, the rows evaluated so far)."""
+    ref = qmm.reference_gemm(x.unsqueeze(0), w.unsqueeze(0))
+    rows = []
+    for fmt, pc in candidates:
+        rows.append(dict(format=fmt, per_channel=pc, **op_error(x, w, fmt, fmt, pc, ref)))
+        if rows[-1]["nsr"] <= nsr_max:
+            return (fmt, pc), rows
+    return None, rows
+
+
 def main():
     names = {v: k for k, v in qmm.FORMATS.items()}
     rows = backward_error_sweep()
@@ -57,6 +97,16 @@ def main():
     for d in range(0, 11):
         sel = (x <= 10.0 ** -d) & (x > 10.0 ** -(d + 1))
         print(f"  1e-{d + 1:<2d}..1e-{d:<2d}" + " ".join(f"{float(prof[f][1][sel].max()):10.3e}" for f in (qmm.INT8, qmm.E4M3, qmm.E5M2)))
+    print("\nnoise-to-signal ratio per op, BERT-large forward shapes (synthetic operands), format x granularity;"
+          " choice = first candidate with NSR <= 1e-3")
+    print(f"{'op':>9s} " + " ".join(f"{names[f] + ('/ch' if pc else '/t'):>10s}" for f, pc in CANDIDATES) + "  choice")
+    for op in W.bert_forward_ops(**W.BERT_LARGE):
+        x, w = W.forward_operands(op, 4, layer=0)
+        xd, wd = x.to("cuda:0"), w.to("cuda:0")
+        rows = format_sweep(xd, wd)
+        choice = next(((r["format"], r["per_channel"]) for r in rows if r["nsr"] <= 1e-3), None)
+        label = "bf16" if choice is None else names[choice[0]] + ("/ch" if choice[1] else "/t")
+        print(f"{op.name:>9s} " + " ".join(f"{r['nsr']:10.3e}" for r in rows) + f"  {label}")
 
 
 if __name__ == "__main__":
