@@ -63,6 +63,7 @@ struct GemmArgs {
     void* y; int y_bf16;              // may be null
     void* acc_out;                    // may be null
     int tiles_m, tiles_n;
+    int direct_along_n;               // gemm_direct_kernel: the workgroup's four wavefronts lie along n (else along m)
     int splits;                       // split-K: workgroups per output tile (1 = none); partial sums go to `partial`
     void* partial;                    // [splits][batch][M][N] raw accumulators (int32 / float)
 };
@@ -677,6 +678,213 @@ gemm_kernel(GemmArgs g)
     }
 }
 
+// An output at most 64 wide or high (attention: probabilities x values, N = head dimension) makes the product
+// HBM-bound: the long operand is read exactly once and nothing of it is reused, so staging it in LDS buys nothing,
+// while a 128 x 128 tile wastes half its columns and its ring admits two workgroups per CU at most.  Here a
+// wavefront loads the fragments of its 64 x 64 block straight from global memory into registers (a lane fetches 32
+// (FP8) or 64 contiguous bytes of a row per slab: whole 128-byte lines per row across the lanes; which K bytes a
+// lane holds only has to agree between the two operands), with no barrier and no LDS, so a dozen wavefronts per
+// CU overlap each other's loads and stores.  The four wavefronts of a workgroup lie along the long side of the
+// output (blocks of 32 rows, i.e. twice the wavefronts, were slower: every wavefront re-reads the short operand).
+// Accumulator and store layout are those of gemm_kernel (a lane owns TILES_N consecutive columns of a row).
+// (Not for short contractions with a large output, e.g. attention scores: there every operand row is wanted by many
+// blocks, and fetching fragments per block through the vector memory path -- sixteen row segments per instruction
+// -- is slower than one LDS copy per workgroup; measured 95 us against 78 us for Q K^T of BERT-large.)
+template <int KIND, int FA, int FB>
+__global__ void __launch_bounds__(256)
+gemm_direct_kernel(GemmArgs g)
+{
+    constexpr bool F8 = (KIND == KIND_F8);
+    constexpr int R = F8 ? 16 : 32;
+    constexpr int WM = 64, WN = 64;
+    constexpr int BLOCKS_M = WM / R, TILES_N = WN / R;
+    constexpr int KS = F8 ? 1 : 4;
+    constexpr int REGS = F8 ? 4 : 16;
+    using AccT = typename std::conditional<F8, v4f, typename std::conditional<KIND == KIND_I8, v16i, v16f>::type>::type;
+    using Frag = typename std::conditional<F8, v8i, v4i>::type;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // the workgroup's wavefronts: 4 x 1 (along m) or 1 x 4 (along n)
+    const int wm = g.direct_along_n ? 0 : wave, wn = g.direct_along_n ? wave : 0;
+    const int BM = g.direct_along_n ? WM : 4 * WM, BN = g.direct_along_n ? 4 * WN : WN;
+
+    const uint32_t tiles_per_batch = (uint32_t)g.tiles_m * (uint32_t)g.tiles_n;
+    const uint32_t total = tiles_per_batch * (uint32_t)g.batch;
+    uint32_t pid = blockIdx.x;
+    {   // each XCD (own L2) takes one contiguous range of the tile sequence
+        const uint32_t per = (total + kNumXcd - 1) / kNumXcd, tall = total % kNumXcd;
+        const uint32_t xcd = pid % kNumXcd, loc = pid / kNumXcd;
+        pid = (tall == 0 || xcd < tall) ? xcd * per + loc : tall * per + (xcd - tall) * (per - 1) + loc;
+    }
+    const int64_t bidx = __builtin_amdgcn_readfirstlane((int)(pid / tiles_per_batch));
+    const uint32_t t = pid - (uint32_t)bidx * tiles_per_batch;
+    const int64_t tile_m = __builtin_amdgcn_readfirstlane((int)(t / (uint32_t)g.tiles_n));
+    const int64_t tile_n = __builtin_amdgcn_readfirstlane((int)(t % (uint32_t)g.tiles_n));
+    const int64_t m_base = tile_m * BM + wm * WM, n_base = tile_n * BN + wn * WN;
+    if (m_base >= g.M || n_base >= g.N) return;          // nothing of this wavefront's block lies inside the output
+
+    // lane (r, h): row r of an operand block; K bytes [W*h, W*h + W) of a slab, W = 32 (FP8: h = 0..3) or 64 (h = 0, 1)
+    const int frow = lane & (R - 1);
+    const int fsel = F8 ? (lane >> 4) : (lane >> 5);
+    const int kofs = fsel * (F8 ? 32 : 64);
+    const int rowbytes = (int)g.rowbytes;
+    const uint8_t* a_rows[BLOCKS_M];
+    const uint8_t* b_rows[TILES_N];
+#pragma unroll
+    for (int i = 0; i < BLOCKS_M; ++i) {
+        int64_t row = m_base + i * R + frow;
+        row = row < g.M ? row : g.M - 1;
+        a_rows[i] = g.a + (bidx * g.M + row) * g.rowbytes + kofs;
+    }
+#pragma unroll
+    for (int j = 0; j < TILES_N; ++j) {
+        int64_t row = n_base + TILES_N * frow + j;      // block j, lane row r  <->  output column TILES_N * r + j
+        row = row < g.N ? row : g.N - 1;
+        b_rows[j] = g.b + (bidx * g.N + row) * g.rowbytes + kofs;
+    }
+
+    AccT acc[BLOCKS_M][TILES_N];
+#pragma unroll
+    for (int i = 0; i < BLOCKS_M; ++i)
+#pragma unroll
+        for (int j = 0; j < TILES_N; ++j)
+#pragma unroll
+            for (int e = 0; e < REGS; ++e) acc[i][j][e] = 0;
+
+    // 16 bytes at byte k of a row, zeros past the end of the row (K is a multiple of 16 bytes: host check)
+    auto load16 = [&](const uint8_t* row_ptr, int k) -> v4i {
+        if (k + kofs < rowbytes) return *reinterpret_cast<const v4i*>(row_ptr + k);
+        return v4i{0, 0, 0, 0};
+    };
+    auto load_frags = [&](const uint8_t* row_ptr, int k0, Frag (&f)[KS]) {
+        if constexpr (F8) {
+            const v4i p0 = load16(row_ptr, k0), p1 = load16(row_ptr, k0 + 16);
+            f[0] = v8i{p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
+        } else {
+#pragma unroll
+            for (int s = 0; s < KS; ++s) f[s] = load16(row_ptr, k0 + 16 * s);
+        }
+    };
+    auto mma = [&](const Frag& fa, const Frag& fb, AccT& c) {
+        if constexpr (F8) {
+            c = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fa, fb, c, FA == QMM_FMT_E5M2 ? 1 : 0,
+                                                                 FB == QMM_FMT_E5M2 ? 1 : 0, 0, 0, 0, 0);
+        } else if constexpr (KIND == KIND_I8) {
+            c = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, c, 0, 0, 0);
+        } else {
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fa), __builtin_bit_cast(v8bf, fb), c, 0, 0, 0);
+        }
+    };
+
+    for (int k0 = 0; k0 < rowbytes; k0 += kSlabBytes) {
+        Frag fa[BLOCKS_M][KS], fb[TILES_N][KS];
+#pragma unroll
+        for (int j = 0; j < TILES_N; ++j) load_frags(b_rows[j], k0, fb[j]);
+#pragma unroll
+        for (int i = 0; i < BLOCKS_M; ++i) load_frags(a_rows[i], k0, fa[i]);
+#pragma unroll
+        for (int i = 0; i < BLOCKS_M; ++i)
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+#pragma unroll
+                for (int j = 0; j < TILES_N; ++j) mma(fa[i][s], fb[j][s], acc[i][j]);
+    }
+
+    // ---- epilogue: (acc * deltaA[row]) * deltaB[column], in that order
+    const float* da = g.da ? g.da + (bidx % g.da_groups) * (g.da_per_channel ? g.M : 1) : nullptr;
+    const float* db = g.db ? g.db + (bidx % g.db_groups) * (g.db_per_channel ? g.N : 1) : nullptr;
+    constexpr bool descale = (KIND != KIND_BF16);
+    const int64_t n = n_base + TILES_N * (lane & (R - 1));
+    const int lane_row = F8 ? 4 * (lane >> 4) : 4 * (lane >> 5);
+    float sr[TILES_N];
+#pragma unroll
+    for (int tt = 0; tt < TILES_N; ++tt) {
+        sr[tt] = 1.0f;
+        if constexpr (descale) sr[tt] = g.db_per_channel ? db[(n + tt) < g.N ? (n + tt) : (g.N - 1)] : db[0];
+    }
+    float sa_scalar = 1.0f;
+    if constexpr (descale) { if (!g.da_per_channel) sa_scalar = da[0]; }
+    auto row_in_block = [&](int r) -> int { return F8 ? lane_row + r : 8 * (r >> 2) + lane_row + (r & 3); };
+    auto raw_of = [&](int ia, int r, int tt) -> uint32_t {
+        if constexpr (KIND == KIND_I8) return (uint32_t)acc[ia][tt][r];
+        else return __float_as_uint(acc[ia][tt][r]);
+    };
+    auto value = [&](int ia, int r, int tt, float sl) -> float {
+        float a;
+        if constexpr (KIND == KIND_I8) a = (float)acc[ia][tt][r];
+        else a = acc[ia][tt][r];
+        if constexpr (descale) a = (a * sl) * sr[tt];
+        return a;
+    };
+    const bool interior = (m_base + WM <= g.M) && (n_base + WN <= g.N) && (g.N % TILES_N == 0);
+    const bool fast = interior && g.y && !g.acc_out;
+    // row step sizes are fetched before the first store (loads and stores share one in-order counter)
+    float sl_rows[BLOCKS_M][REGS];
+#pragma unroll
+    for (int ia = 0; ia < BLOCKS_M; ++ia)
+#pragma unroll
+        for (int r = 0; r < REGS; ++r) {
+            sl_rows[ia][r] = sa_scalar;
+            if constexpr (descale) {
+                if (g.da_per_channel) {
+                    const int64_t m = m_base + ia * R + row_in_block(r);
+                    sl_rows[ia][r] = da[m < g.M ? m : g.M - 1];
+                }
+            }
+        }
+    if (fast && g.y_bf16) {
+        uint8_t* ybase = static_cast<uint8_t*>(g.y) + ((bidx * g.M + m_base) * g.N + n) * 2;
+#pragma unroll
+        for (int ia = 0; ia < BLOCKS_M; ++ia)
+#pragma unroll
+            for (int r = 0; r < REGS; ++r) {
+                typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+                typedef float f2 __attribute__((ext_vector_type(2)));
+                uint32_t pk[TILES_N / 2];
+#pragma unroll
+                for (int q = 0; q < TILES_N / 2; ++q)
+                    pk[q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(
+                        f2{value(ia, r, 2 * q, sl_rows[ia][r]), value(ia, r, 2 * q + 1, sl_rows[ia][r])}, bf2));
+                uint8_t* dst = ybase + (int64_t)(ia * R + row_in_block(r)) * g.N * 2;
+                if constexpr (TILES_N == 4) *reinterpret_cast<u32x2*>(dst) = u32x2{pk[0], pk[1]};
+                else *reinterpret_cast<uint32_t*>(dst) = pk[0];
+            }
+    } else if (fast && TILES_N == 4) {
+        float* ybase = static_cast<float*>(g.y) + (bidx * g.M + m_base) * g.N + n;
+#pragma unroll
+        for (int ia = 0; ia < BLOCKS_M; ++ia)
+#pragma unroll
+            for (int r = 0; r < REGS; ++r) {
+                v4f v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = value(ia, r, e < TILES_N ? e : 0, sl_rows[ia][r]);
+                *reinterpret_cast<v4f*>(ybase + (int64_t)(ia * R + row_in_block(r)) * g.N) = v;
+            }
+    } else if (n < g.N) {
+#pragma unroll
+        for (int ia = 0; ia < BLOCKS_M; ++ia)
+#pragma unroll
+            for (int r = 0; r < REGS; ++r) {
+                const int64_t m = m_base + ia * R + row_in_block(r);
+                if (m < g.M) {
+                    const int64_t o = (bidx * g.M + m) * g.N + n;
+#pragma unroll
+                    for (int tt = 0; tt < TILES_N; ++tt) {
+                        if (n + tt < g.N) {
+                            const float v = value(ia, r, tt, sl_rows[ia][r]);
+                            if (g.acc_out) static_cast<uint32_t*>(g.acc_out)[o + tt] = raw_of(ia, r, tt);
+                            if (g.y) {
+                                if (g.y_bf16) static_cast<__bf16*>(g.y)[o + tt] = (__bf16)v;
+                                else static_cast<float*>(g.y)[o + tt] = v;
+                            }
+                        }
+                    }
+                }
+            }
+    }
+}
+
 // Second kernel of split-K: out = descale(sum over the K ranges, in ascending order, of the partial accumulators).
 // INT8 partials are integers (the sum is exact); FP8 / bfloat16 partials are binary32 and added in binary32.
 // One thread per four consecutive columns.
@@ -769,9 +977,34 @@ qmm_status launch_tile(GemmArgs& g, hipStream_t s)
     return launch_status();
 }
 
+template <int KIND, int FA, int FB>
+qmm_status launch_direct(GemmArgs& g, hipStream_t s)
+{
+    g.direct_along_n = (g.M <= 64 && g.N > 64) ? 1 : 0;
+    const int bm = g.direct_along_n ? 64 : 256, bn = g.direct_along_n ? 256 : 64;
+    g.tiles_m = (int)((g.M + bm - 1) / bm);
+    g.tiles_n = (int)((g.N + bn - 1) / bn);
+    const int64_t total = (int64_t)g.tiles_m * g.tiles_n * g.batch;
+    if (total > 0x7FFFFFFF) return QMM_ERR_UNSUPPORTED;
+    gemm_direct_kernel<KIND, FA, FB><<<(unsigned)total, 256, 0, s>>>(g);
+    return launch_status();
+}
+
+// True for the shapes gemm_direct_kernel is for: codes in, no split, an output at most 64 wide or high, and enough
+// 64 x 64 blocks to give every CU a couple of wavefronts.
+bool use_direct(const GemmArgs& g, int fuse)
+{
+    if (fuse != 0 || g.splits > 1) return false;
+    const int64_t blocks = ((g.M + 63) / 64) * ((g.N + 63) / 64) * g.batch;
+    return blocks >= 512 && (g.M <= 64 || g.N <= 64);
+}
+
 template <int KIND, int FA, int FB, int FUSE>
 qmm_status launch_fuse(GemmArgs& g, hipStream_t s)
 {
+    if constexpr (FUSE == 0) {
+        if (use_direct(g, 0)) return launch_direct<KIND, FA, FB>(g, s);
+    }
     // 256 x 256 tiles (eight wavefronts, two per SIMD: while one waits at a copy or a fragment read the other
     // issues matrix instructions) when they still give every CU work, else 128 x 128 tiles (four wavefronts, two
     // workgroups per CU).

@@ -162,9 +162,13 @@ GEMM_SHAPES = [(1, 16, 16, 16), (1, 128, 128, 128), (1, 256, 768, 768), (1, 200,
                (3, 130, 80, 64), (1, 520, 528, 1040), (2, 257, 512, 272), (1, 64, 1000, 48),
                # long K, few tiles: the split-K path (partial sums per K range, reduced in a fixed order)
                (1, 64, 96, 4096), (2, 100, 72, 2064), (1, 300, 272, 2048)]
+# many small matrices with a contraction of one slab at most (attention scores), and outputs at most 64 wide / high
+# (probabilities x values): the latter take the kernel that loads operand fragments straight into registers (ragged
+# edges, ragged K, both skinny directions, a whole-block interior case)
+DIRECT_SHAPES = [(36, 250, 250, 64), (32, 256, 256, 48), (66, 500, 40, 144), (66, 40, 500, 144), (40, 512, 64, 128)]
 
 
-@pytest.mark.parametrize("shape", GEMM_SHAPES)
+@pytest.mark.parametrize("shape", GEMM_SHAPES + DIRECT_SHAPES)
 def test_gemm_int8_bit_exact(shape):
     bt, M, N, K = shape
     a = _random_codes(O.INT8, (bt, M, K), 1); b = _random_codes(O.INT8, (bt, N, K), 2)
@@ -200,6 +204,12 @@ def test_gemm_int8_worst_case_and_one_hot():
         _, acc = qmm.gemm((ta, qmm.operand(ta, qmm.INT8, one)), (tb, qmm.operand(tb, qmm.INT8, one)), want_acc=True)
         acc = acc.cpu().numpy()
         assert acc[0, i, j] == va * vb and np.count_nonzero(acc) == 1, (i, j, k)
+
+
+@pytest.mark.parametrize("shape", DIRECT_SHAPES)
+@pytest.mark.parametrize("fa,fb", [(qmm.E4M3, qmm.E4M3), (qmm.E5M2, qmm.E4M3)])
+def test_gemm_fp8_direct_kernel_within_tolerance(shape, fa, fb):
+    test_gemm_fp8_within_tolerance(shape, fa, fb)
 
 
 @pytest.mark.parametrize("shape", GEMM_SHAPES)
@@ -301,7 +311,8 @@ def test_gemm_quantize_on_load_matches_separate_quantize(shape, fa, fb, per_chan
 
 
 def test_reference_gemm():
-    for (bt, M, N, K) in [(1, 256, 768, 768), (2, 100, 72, 200), (1, 130, 258, 520), (1, 200, 264, 4104)]:   # last: split-K
+    for (bt, M, N, K) in [(1, 256, 768, 768), (2, 100, 72, 200), (1, 130, 258, 520), (1, 200, 264, 4104),   # last: split-K
+                          (36, 250, 250, 56), (66, 500, 40, 72)]:                     # fragments straight to registers
         x = W.normal((bt, M, K), 1.0, 5); w = W.normal((bt, N, K), 0.02, 6)
         r = qmm.reference_gemm(x.to(DEV), w.to(DEV)).cpu().numpy()
         want = O.ref_gemm(np32(x), np32(w))
