@@ -4,9 +4,10 @@
 // plus the bfloat16 pass-through product used as the high-precision reference.
 //
 // Design (gfx950, wave64, MFMA):
-//  * Workgroup = 4 wavefronts in a 2 x 2 grid; one wavefront owns 32*TM rows (m)
-//    by 64*TG columns (n) of the output in accumulator registers (128 x 128 for
-//    the large tile: 256 AGPRs).
+//  * Workgroup = 2 x NWN wavefronts; one wavefront owns 32*TM rows (m) by 64*TG
+//    columns (n) of the output in accumulator registers.  Large tile: 256 x 256,
+//    eight wavefronts of 128 x 64 (128 AGPRs each), two per SIMD; small tile:
+//    128 x 128, four wavefronts.
 //  * Operands are [rows][K] with K contiguous.  A K-slab of 128 bytes per row is
 //    staged in LDS as plain 128-byte rows; the 16-byte chunk c of LDS row p sits
 //    at chunk position c ^ ((p >> 1) & 7).  global_load_lds_dwordx4 copies
@@ -20,14 +21,18 @@
 //    bfloat16 v_mfma_f32_32x32x16_bf16 (measured on this part: the 16x16 forms of
 //    those two issue at ~60 % of the 32x32 rate).  Which K bytes a lane holds is
 //    the same for both operands, which is all a contraction needs.
-//  * The B matrix (n) feeds the MFMA's first operand and A (m) the second, so a
+//  * The A matrix (m) feeds the MFMA's first operand and B (n) the second, so a
 //    lane ends up holding several n of one m.  The rows of a B block are picked
-//    from global memory in a permuted order such that a lane's values are 16
-//    consecutive columns per 64-column group half: stores are 32 (bf16) or 64
-//    (fp32) contiguous bytes per lane and whole 128-byte lines per row.
-//  * Two LDS stages; the slab for step k+1 is in flight while step k multiplies.
+//    from global memory in a permuted order such that a lane's values are TILES_N
+//    consecutive columns: stores are 8 or 16 contiguous bytes per lane and whole
+//    128-byte lines per row across the lanes.
+//  * LDS holds a ring of three A slabs and two B slabs; the B fragments of the
+//    current slab sit in registers for the whole K step.  One barrier per step;
+//    copies are requested one at a time between matrix instructions.
 //  * Workgroup ids are spread so that each XCD (own L2) walks a compact band of
 //    tiles.
+//  * Long K with few tiles: split-K with a second, fixed-order reduction kernel.
+//    Outputs at most 64 wide or high: gemm_direct_kernel (no LDS).
 #include <type_traits>
 
 #include "qmm_device.h"
