@@ -227,6 +227,39 @@ def main():
               for k in ("scale", "quantize", "metric", "moments")}
     nsr = {st["op"].name: float(st["m"][0].item() / st["m"][1].item()) for st in state}
 
+    # ---- the memory-bound passes on the step's largest tensors alone, free of launch latency: ten launches back to
+    #      back per event pair, rotating over three copies of the operand (more bytes than the 256 MB memory-side
+    #      cache holds, so every launch reads HBM); the metric's inputs are larger than that cache by themselves
+    def passes_on_largest():
+        big_x = max(state, key=lambda st: st["x"].numel())
+        xs = [big_x["x"]] + [big_x["x"].clone() for _ in range(2)]
+        cs = [torch.empty_like(big_x["cx"]) for _ in range(3)]
+        big_y = max(state, key=lambda st: st["y"].numel())
+        nx, ny = big_x["x"].numel(), big_y["y"].numel()
+        ws, dx, m = big_x["ws"], big_x["dx"], big_y["m"]
+        qmm.scale(xs[0], 1, fmt, out=dx, workspace=ws)
+
+        def rate(nbytes, fn):
+            ts = []
+            for it in range(4):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for k in range(10):
+                    fn(k % 3)
+                e1.record()
+                torch.cuda.synchronize()
+                if it >= 1:
+                    ts.append(e0.elapsed_time(e1) / 10)
+            ms = sorted(ts)[len(ts) // 2]
+            return {"bytes_per_launch": nbytes, "ms_per_launch": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                    "frac_hbm": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        return {"what": "largest X of the step (scale, quantize) and largest Y (metric), 10 launches back to back per "
+                        "event pair, operands rotated over 3 copies",
+                "scale": rate(2 * nx, lambda k: qmm.scale(xs[k], 1, fmt, out=dx, workspace=ws)),
+                "quantize": rate(3 * nx, lambda k: qmm.quantize(xs[k], 1, fmt, dx, out=cs[k])),
+                "metric": rate(6 * ny, lambda k: qmm.metric(big_y["y"], big_y["y_ref"], out=m, workspace=ws))}
+    passes["largest_tensors"] = passes_on_largest()
+
     # ---- the oracle timed on the host cores, on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline:
