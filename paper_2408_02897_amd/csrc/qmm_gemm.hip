@@ -104,6 +104,21 @@ template <int N> QMM_DEV void wait_vm_lgkm()
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(N) : "memory");
 }
 
+// The matrix instructions below are inline assembly, so the compiler does not know that they read the accumulator
+// registers as MFMA operands: left alone it sinks the zero initialisation (v_accvgpr_write) to just in front of
+// the first such statement that uses a block, closer than the wait states an MFMA needs after such a write.  An
+// empty volatile statement with every block as an in-out AGPR operand makes the initialisation happen here;
+// volatile statements keep their order, so the s_nop that follows it really separates the two.
+template <typename AccT, int NI, int NJ> QMM_DEV void pin_accumulators(AccT (&acc)[NI][NJ])
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) asm volatile("" : "+a"(acc[i][j]));
+#endif
+}
+
 // FUSE: bit 0 / bit 1 = the A / B operand arrives as bfloat16 values and is quantized (RTNE, with its step sizes)
 // while it is staged into LDS; otherwise it arrives as 8-bit codes and is copied by LDS-DMA.
 // NWN: wavefronts along N (2 or 4): the workgroup has 2 x NWN wavefronts, NWN / 2 on every SIMD.
@@ -308,6 +323,7 @@ gemm_kernel(GemmArgs g)
         for (int j = 0; j < TILES_N; ++j)
 #pragma unroll
             for (int e = 0; e < (F8 ? 4 : 16); ++e) acc[i][j][e] = 0;
+    pin_accumulators(acc);
 
     // FP8: lane (r = l%16, g = l/16) reads chunks g and g+4 of row r of a 16-row block.
     // INT8/BF16: lane (r = l%32, h = l/32) reads chunk 2s+h of row r of a 32-row block for K slice s = 0..3.
@@ -598,21 +614,23 @@ gemm_kernel(GemmArgs g)
                     for (int r = 0; r < REGS; ++r) sl_rows[ia][r] = da[m_base + ia * R + row_in_block(r)];
             }
         }
+        typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        auto packed_row = [&](int ia, int r, uint32_t (&pk)[TILES_N / 2]) {
+#pragma unroll
+            for (int q = 0; q < TILES_N / 2; ++q) {
+                uint32_t raw0, raw1;
+                const float v0 = value(ia, r, 2 * q, sl_rows[ia][r], raw0), v1 = value(ia, r, 2 * q + 1, sl_rows[ia][r], raw1);
+                pk[q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{v0, v1}, bf2));
+            }
+        };
 #pragma unroll
         for (int ia = 0; ia < BLOCKS_M; ++ia) {
 #pragma unroll
             for (int r = 0; r < REGS; ++r) {
                 const int ml = ia * R + row_in_block(r);
-                const float sl = sl_rows[ia][r];
-                typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
-                typedef float f2 __attribute__((ext_vector_type(2)));
                 uint32_t pk[TILES_N / 2];
-#pragma unroll
-                for (int q = 0; q < TILES_N / 2; ++q) {
-                    uint32_t raw0, raw1;
-                    const float v0 = value(ia, r, 2 * q, sl, raw0), v1 = value(ia, r, 2 * q + 1, sl, raw1);
-                    pk[q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{v0, v1}, bf2));
-                }
+                packed_row(ia, r, pk);
                 uint8_t* dst = ybase + ml * row_bytes;
                 if constexpr (TILES_N == 8) *reinterpret_cast<u32x4*>(dst) = u32x4{pk[0], pk[1], pk[2], pk[3]};
                 else if constexpr (TILES_N == 4) *reinterpret_cast<u32x2*>(dst) = u32x2{pk[0], pk[1]};
@@ -680,6 +698,276 @@ gemm_kernel(GemmArgs g)
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+    }
+}
+
+// Contraction of one slab at most (attention scores: K = head dimension) with a large output.  A tile of
+// gemm_kernel would be: copies, wait a memory latency, 32 matrix instructions per wavefront, 128 KB of stores -- and
+// with one workgroup per CU nothing overlaps, so the latency and the stores are paid in full for every tile.  Here
+// the workgroup stays on its CU and walks tiles; LDS holds two slabs of each operand, and the copies of the next
+// tile are requested right after the barrier that starts the current one, so they land behind its matrix
+// instructions and stores.  Same tile (256 x 256, eight wavefronts), LDS layout, fragment reads and accumulator
+// layout as gemm_kernel; whole tiles only (the host sends ragged shapes to gemm_kernel).
+// Order of a wavefront's vector-memory operations: copies(t+1), stores(t), copies(t+2), ...; they complete in order,
+// so "at most the stores of tile t outstanding" at the top of tile t+1 means its copies have landed.
+template <int KIND, int FA, int FB>
+__global__ void __launch_bounds__(512, 1)
+gemm_shortk_kernel(GemmArgs g)
+{
+    constexpr bool F8 = (KIND == KIND_F8);
+    constexpr int NWN = 4, NWAVES = 8;
+    constexpr int BM = 256, BN = 256, WM = 128, WN = 64;
+    constexpr int R = F8 ? 16 : 32;
+    constexpr int BLOCKS_M = WM / R, TILES_N = WN / R;
+    constexpr int KS = F8 ? 1 : 4;
+    constexpr int REGS = F8 ? 4 : 16;
+    constexpr int A_SLOT = BM * kSlabBytes, B_SLOT = BN * kSlabBytes;
+    constexpr int B_BASE = 2 * A_SLOT;
+    constexpr int A_PER_WAVE = BM / 8 / NWAVES, B_PER_WAVE = BN / 8 / NWAVES;
+    constexpr int STORES = BLOCKS_M * REGS;          // store instructions of one tile's epilogue, one per row and lane
+    using AccT = typename std::conditional<F8, v4f, typename std::conditional<KIND == KIND_I8, v16i, v16f>::type>::type;
+    using Frag = typename std::conditional<F8, v8i, v4i>::type;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / NWN, wn = wave % NWN;
+    const int rowbytes = (int)g.rowbytes;                       // <= kSlabBytes
+    const uint32_t tiles_per_batch = (uint32_t)g.tiles_m * (uint32_t)g.tiles_n;
+    const uint32_t total = tiles_per_batch * (uint32_t)g.batch;
+
+    // ---- copy sources (32-bit byte offsets from a tile's first A / B row) and LDS targets, as in gemm_kernel
+    uint32_t a_src[A_PER_WAVE], b_src[B_PER_WAVE];
+    bool a_live[A_PER_WAVE], b_live[B_PER_WAVE];                // false: this lane's chunk lies past the end of the row
+#pragma unroll
+    for (int i = 0; i < A_PER_WAVE; ++i) {
+        const int p = (wave * A_PER_WAVE + i) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((p >> 1) & 7);
+        a_src[i] = (uint32_t)(p * rowbytes + c * 16);
+        a_live[i] = c * 16 < rowbytes;
+    }
+#pragma unroll
+    for (int i = 0; i < B_PER_WAVE; ++i) {
+        const int p = (wave * B_PER_WAVE + i) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((p >> 1) & 7);
+        const int row = WN * (p / WN) + TILES_N * (p % R) + (p / R) % TILES_N;
+        b_src[i] = (uint32_t)(row * rowbytes + c * 16);
+        b_live[i] = c * 16 < rowbytes;
+    }
+    typedef __attribute__((address_space(3))) uint8_t* lds_ptr_t;
+    const uint32_t lds_a_units = (uint32_t)(uintptr_t)(lds_ptr_t)(lds + wave * A_PER_WAVE * 1024);
+    const uint32_t lds_b_units = (uint32_t)(uintptr_t)(lds_ptr_t)(lds + B_BASE + wave * B_PER_WAVE * 1024);
+    // Places in LDS whose chunk lies past the end of the rows never receive a copy: zeroed once, in both slots.
+#pragma unroll
+    for (int slot = 0; slot < 2; ++slot) {
+#pragma unroll
+        for (int i = 0; i < A_PER_WAVE; ++i)
+            if (!a_live[i]) *reinterpret_cast<u32x4*>(lds + slot * A_SLOT + (wave * A_PER_WAVE + i) * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < B_PER_WAVE; ++i)
+            if (!b_live[i]) *reinterpret_cast<u32x4*>(lds + B_BASE + slot * B_SLOT + (wave * B_PER_WAVE + i) * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+    }
+
+    // tile number -> first A row, first B row (scalar), output coordinates
+    struct Tile { const uint8_t* a; const uint8_t* b; int64_t bidx, m0, n0; };
+    auto tile_of = [&](uint32_t t) -> Tile {
+        const int64_t bidx = __builtin_amdgcn_readfirstlane((int)(t / tiles_per_batch));
+        const uint32_t r = t - (uint32_t)bidx * tiles_per_batch;
+        const int64_t tm = __builtin_amdgcn_readfirstlane((int)(r / (uint32_t)g.tiles_n));
+        const int64_t tn = __builtin_amdgcn_readfirstlane((int)(r % (uint32_t)g.tiles_n));
+        Tile o;
+        o.bidx = bidx; o.m0 = tm * BM; o.n0 = tn * BN;
+        o.a = g.a + (bidx * g.M + o.m0) * g.rowbytes;
+        o.b = g.b + (bidx * g.N + o.n0) * g.rowbytes;
+        return o;
+    };
+    auto issue_copies = [&](const Tile& t, int slot) {
+#pragma unroll
+        for (int i = 0; i < A_PER_WAVE; ++i)
+            if (a_live[i]) dma16_uniform(t.a, a_src[i], lds_a_units + slot * A_SLOT + i * 1024);
+#pragma unroll
+        for (int i = 0; i < B_PER_WAVE; ++i)
+            if (b_live[i]) dma16_uniform(t.b, b_src[i], lds_b_units + slot * B_SLOT + i * 1024);
+    };
+
+    // ---- fragments (as in gemm_kernel)
+    const int frow = lane & (R - 1);
+    const int fkey = (frow >> 1) & 7;
+    const int fsel = F8 ? (lane >> 4) : (lane >> 5);
+    const int a_off = (wm * WM + frow) * kSlabBytes;
+    const int b_off = B_BASE + (wn * WN + frow) * kSlabBytes;
+    int coff[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) coff[s] = ((F8 ? fsel : 2 * s + fsel) ^ fkey) * 16;
+    auto read_frag = [&](const uint8_t* row_ptr, int s) -> Frag {
+        if constexpr (F8) {
+            const v4i p0 = *reinterpret_cast<const v4i*>(row_ptr + coff[0]);
+            const v4i p1 = *reinterpret_cast<const v4i*>(row_ptr + (coff[0] ^ 64));
+            return v8i{p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
+        } else {
+            return *reinterpret_cast<const v4i*>(row_ptr + coff[s]);
+        }
+    };
+    auto mma = [&](const Frag& fa, const Frag& fb, AccT& c) {
+#if defined(__HIP_DEVICE_COMPILE__)
+        if constexpr (F8) {
+            if constexpr (FA == QMM_FMT_E5M2 && FB == QMM_FMT_E5M2)
+                asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 cbsz:1 blgp:1" : "+a"(c) : "v"(fa), "v"(fb));
+            else if constexpr (FA == QMM_FMT_E5M2)
+                asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 cbsz:1" : "+a"(c) : "v"(fa), "v"(fb));
+            else if constexpr (FB == QMM_FMT_E5M2)
+                asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 blgp:1" : "+a"(c) : "v"(fa), "v"(fb));
+            else
+                asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(c) : "v"(fa), "v"(fb));
+        } else if constexpr (KIND == KIND_I8) {
+            asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+a"(c) : "v"(fa), "v"(fb));
+        } else {
+            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(fa), "v"(fb));
+        }
+#endif
+    };
+
+    AccT acc[BLOCKS_M][TILES_N];
+    constexpr bool descale = (KIND != KIND_BF16);
+
+    const uint32_t stride = gridDim.x;
+    uint32_t t_cur = blockIdx.x;
+    if (t_cur >= total) return;
+    Tile cur = tile_of(t_cur);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // the zeroing above
+    issue_copies(cur, 0);
+    for (int it = 0;; ++it) {
+        const int slot = it & 1;
+#pragma unroll
+        for (int i = 0; i < BLOCKS_M; ++i)
+#pragma unroll
+            for (int j = 0; j < TILES_N; ++j)
+#pragma unroll
+                for (int e = 0; e < REGS; ++e) acc[i][j][e] = 0;
+        pin_accumulators(acc);
+        // this tile's copies have landed (the stores of the tile before, issued after them, may still be under way)
+        // (the count must not exceed the number of operations issued after those copies -- "at most n outstanding"
+        // says nothing about the n newest -- so it is the exact number of stores of the path taken, or less)
+        if (it == 0) wait_vm_lgkm<0>(); else wait_vm_lgkm<(STORES > 63 ? 63 : STORES)>();
+        __syncthreads();
+        // every wavefront has left the tile before: its slot is free for the tile after this one
+        const uint32_t t_next = t_cur + stride;
+        const bool has_next = t_next < total;
+        Tile nxt = cur;
+        if (has_next) {
+            nxt = tile_of(t_next);
+            issue_copies(nxt, slot ^ 1);
+        }
+        Frag fb[KS][TILES_N], fa[2][KS];
+        {
+            const uint8_t* sb = lds + slot * B_SLOT + b_off;
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+#pragma unroll
+                for (int j = 0; j < TILES_N; ++j) fb[s][j] = read_frag(sb + j * R * kSlabBytes, s);
+        }
+        const uint8_t* sa = lds + slot * A_SLOT + a_off;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) fa[0][s] = read_frag(sa, s);
+        asm volatile("s_nop 7" ::: "memory");     // accumulator initialisation -> first matrix instruction
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < BLOCKS_M; ++i) {
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+#pragma unroll
+                for (int j = 0; j < TILES_N; ++j) {
+                    mma(fa[i & 1][s], fb[s][j], acc[i][j]);
+                    if (s == 0 && j == 0 && i + 1 < BLOCKS_M) {
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int s2 = 0; s2 < KS; ++s2) fa[(i + 1) & 1][s2] = read_frag(sa + (i + 1) * R * kSlabBytes, s2);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // wait states between the last matrix instruction and the first read of an accumulator
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- epilogue of a whole tile: (acc * deltaA[row]) * deltaB[column], in that order
+        {
+            const int64_t bidx = cur.bidx;
+            const int64_t m_base = cur.m0 + wm * WM, n_base = cur.n0 + wn * WN;
+            const float* da = g.da ? g.da + (bidx % g.da_groups) * (g.da_per_channel ? g.M : 1) : nullptr;
+            const float* db = g.db ? g.db + (bidx % g.db_groups) * (g.db_per_channel ? g.N : 1) : nullptr;
+            int lane_e = lane;                    // kept out of the loop-invariant code the compiler would hoist
+            asm volatile("" : "+v"(lane_e));
+            const int64_t n = n_base + TILES_N * (lane_e & (R - 1));
+            const int lane_row = F8 ? 4 * (lane_e >> 4) : 4 * (lane_e >> 5);
+            auto row_in_block = [&](int r) -> int { return F8 ? lane_row + r : 8 * (r >> 2) + lane_row + (r & 3); };
+            float sr[TILES_N];
+#pragma unroll
+            for (int tt = 0; tt < TILES_N; ++tt) {
+                sr[tt] = 1.0f;
+                if constexpr (descale) sr[tt] = g.db_per_channel ? db[n + tt] : db[0];
+            }
+            float sa_scalar = 1.0f;
+            if constexpr (descale) { if (!g.da_per_channel) sa_scalar = da[0]; }
+            float sl_rows[BLOCKS_M][REGS];
+#pragma unroll
+            for (int ia = 0; ia < BLOCKS_M; ++ia)
+#pragma unroll
+                for (int r = 0; r < REGS; ++r) {
+                    sl_rows[ia][r] = sa_scalar;
+                    if constexpr (descale) { if (g.da_per_channel) sl_rows[ia][r] = da[m_base + ia * R + row_in_block(r)]; }
+                }
+            auto value = [&](int ia, int r, int tt) -> float {
+                uint32_t raw;
+                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(raw) : "a"(acc[ia][tt][r]));
+                float a;
+                if constexpr (KIND == KIND_I8) a = (float)(int32_t)raw;
+                else a = __uint_as_float(raw);
+                if constexpr (descale) a = (a * sl_rows[ia][r]) * sr[tt];
+                return a;
+            };
+            if (g.y_bf16) {
+                uint8_t* ybase = static_cast<uint8_t*>(g.y) + ((bidx * g.M + m_base) * g.N + n) * 2;
+                const int64_t row_bytes = g.N * 2;
+                typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+                typedef float f2 __attribute__((ext_vector_type(2)));
+                auto packed_row = [&](int ia, int r, uint32_t (&pk)[TILES_N / 2]) {
+#pragma unroll
+                    for (int q = 0; q < TILES_N / 2; ++q) {
+                        const float v0 = value(ia, r, 2 * q), v1 = value(ia, r, 2 * q + 1);
+                        pk[q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{v0, v1}, bf2));
+                    }
+                };
+#pragma unroll
+                for (int ia = 0; ia < BLOCKS_M; ++ia) {
+#pragma unroll
+                    for (int r = 0; r < REGS; ++r) {
+                        uint32_t pk[TILES_N / 2];
+                        packed_row(ia, r, pk);
+                        uint8_t* dst = ybase + (ia * R + row_in_block(r)) * row_bytes;
+                        if constexpr (TILES_N == 4) *reinterpret_cast<u32x2*>(dst) = u32x2{pk[0], pk[1]};
+                        else *reinterpret_cast<uint32_t*>(dst) = pk[0];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else if constexpr (TILES_N == 4) {
+                float* ybase = static_cast<float*>(g.y) + (bidx * g.M + m_base) * g.N + n;
+#pragma unroll
+                for (int ia = 0; ia < BLOCKS_M; ++ia) {
+#pragma unroll
+                    for (int r = 0; r < REGS; ++r) {
+                        v4f v;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = value(ia, r, e);
+                        *reinterpret_cast<v4f*>(ybase + (int64_t)(ia * R + row_in_block(r)) * g.N) = v;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        if (!has_next) break;
+        cur = nxt; t_cur = t_next;
     }
 }
 
@@ -1004,11 +1292,42 @@ bool use_direct(const GemmArgs& g, int fuse)
     return blocks >= 512 && (g.M <= 64 || g.N <= 64);
 }
 
+// gemm_shortk_kernel: codes in, no split, one slab of K at most, whole 256 x 256 tiles only, output in y alone
+// (binary32 only where a lane owns four columns), and at least two tiles for every workgroup of the grid.
+constexpr int kShortKGrid = 256;
+template <int KIND>
+bool use_shortk(const GemmArgs& g, int fuse)
+{
+    if (fuse != 0 || g.splits > 1 || g.rowbytes > kSlabBytes) return false;
+    if (g.M % 256 != 0 || g.N % 256 != 0 || !g.y || g.acc_out) return false;
+    if (!g.y_bf16 && KIND != KIND_F8) return false;
+    return (g.M / 256) * (g.N / 256) * g.batch >= 2 * kShortKGrid;
+}
+
+template <int KIND, int FA, int FB>
+qmm_status launch_shortk(GemmArgs& g, hipStream_t s)
+{
+    constexpr int LDS_BYTES = 4 * 256 * kSlabBytes;
+    g.tiles_m = (int)(g.M / 256);
+    g.tiles_n = (int)(g.N / 256);
+    if ((int64_t)g.tiles_m * g.tiles_n * g.batch > 0x7FFFFFFF) return QMM_ERR_UNSUPPORTED;
+    auto kern = gemm_shortk_kernel<KIND, FA, FB>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+            return QMM_ERR_LAUNCH;
+        attr_set = true;
+    }
+    kern<<<kShortKGrid, 512, LDS_BYTES, s>>>(g);
+    return launch_status();
+}
+
 template <int KIND, int FA, int FB, int FUSE>
 qmm_status launch_fuse(GemmArgs& g, hipStream_t s)
 {
     if constexpr (FUSE == 0) {
         if (use_direct(g, 0)) return launch_direct<KIND, FA, FB>(g, s);
+        if (use_shortk<KIND>(g, 0)) return launch_shortk<KIND, FA, FB>(g, s);
     }
     // 256 x 256 tiles (eight wavefronts, two per SIMD: while one waits at a copy or a fragment read the other
     // issues matrix instructions) when they still give every CU work, else 128 x 128 tiles (four wavefronts, two

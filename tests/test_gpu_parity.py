@@ -168,7 +168,12 @@ GEMM_SHAPES = [(1, 16, 16, 16), (1, 128, 128, 128), (1, 256, 768, 768), (1, 200,
 DIRECT_SHAPES = [(36, 250, 250, 64), (32, 256, 256, 48), (66, 500, 40, 144), (66, 40, 500, 144), (40, 512, 64, 128)]
 
 
-@pytest.mark.parametrize("shape", GEMM_SHAPES + DIRECT_SHAPES)
+# a contraction of one slab at most, whole 256 x 256 tiles, at least 512 of them: the kernel whose workgroups stay
+# on their CU and fetch the next tile behind the current one (K = 64, a ragged 48, a full slab)
+SHORTK_SHAPES = [(128, 512, 512, 64), (70, 1024, 512, 48), (64, 768, 768, 128)]
+
+
+@pytest.mark.parametrize("shape", GEMM_SHAPES + DIRECT_SHAPES + SHORTK_SHAPES)
 def test_gemm_int8_bit_exact(shape):
     bt, M, N, K = shape
     a = _random_codes(O.INT8, (bt, M, K), 1); b = _random_codes(O.INT8, (bt, N, K), 2)
@@ -206,7 +211,7 @@ def test_gemm_int8_worst_case_and_one_hot():
         assert acc[0, i, j] == va * vb and np.count_nonzero(acc) == 1, (i, j, k)
 
 
-@pytest.mark.parametrize("shape", DIRECT_SHAPES)
+@pytest.mark.parametrize("shape", DIRECT_SHAPES + [(128, 512, 512, 32), (64, 512, 1024, 48)])
 @pytest.mark.parametrize("fa,fb", [(qmm.E4M3, qmm.E4M3), (qmm.E5M2, qmm.E4M3)])
 def test_gemm_fp8_direct_kernel_within_tolerance(shape, fa, fb):
     test_gemm_fp8_within_tolerance(shape, fa, fb)
@@ -312,7 +317,8 @@ def test_gemm_quantize_on_load_matches_separate_quantize(shape, fa, fb, per_chan
 
 def test_reference_gemm():
     for (bt, M, N, K) in [(1, 256, 768, 768), (2, 100, 72, 200), (1, 130, 258, 520), (1, 200, 264, 4104),   # last: split-K
-                          (36, 250, 250, 56), (66, 500, 40, 72)]:                     # fragments straight to registers
+                          (36, 250, 250, 56), (66, 500, 40, 72),                      # fragments straight to registers
+                          (128, 512, 512, 40)]:                                       # short K, resident workgroups
         x = W.normal((bt, M, K), 1.0, 5); w = W.normal((bt, N, K), 0.02, 6)
         r = qmm.reference_gemm(x.to(DEV), w.to(DEV)).cpu().numpy()
         want = O.ref_gemm(np32(x), np32(w))
