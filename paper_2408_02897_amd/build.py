@@ -1,8 +1,10 @@
 """Build libqmm.so (HIP, gfx950 only) in-tree with hipcc.
 
     python -m paper_2408_02897_amd.build [--force]
+    python -m paper_2408_02897_amd.build --check-asm     # scan the GEMM kernels' assembly (a few minutes)
 """
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -38,5 +40,54 @@ def build(force=False):
     return LIB
 
 
+def check_asm():
+    """Compile qmm_gemm.hip to gfx950 assembly and check what the compiler cannot know about the inline-assembly
+    matrix instructions and copies: (1) no accumulator register is written by v_accvgpr_write within six
+    instructions in front of an MFMA that uses it (wait states), (2) every LDS copy has its base address in scalar
+    registers, (3) no MFMA goes through v_accvgpr_mov copies inside the loops (at most one initialisation pass), (4) the
+    kernels on the throughput path use no scratch memory.  Returns a list of findings (empty = clean)."""
+    os.makedirs(OBJDIR, exist_ok=True)
+    asm = os.path.join(OBJDIR, "qmm_gemm.s")
+    subprocess.run([HIPCC, *[f for f in FLAGS if f != "-fPIC"], "--cuda-device-only", "-S",
+                    os.path.join(CSRC, "qmm_gemm.hip"), "-o", asm], check=True)
+    text = open(asm).read()
+    findings = []
+    names = list(dict.fromkeys(re.findall(r"^(_ZN3qmm\S*(?:gemm_kernel|gemm_shortk_kernel)\S*):", text, flags=re.M)))
+    for nm in names:
+        start = text.index("\n" + nm + ":")
+        end = text.index(".Lfunc_end", start)
+        body = text[start:end]
+        instrs = [l.strip() for l in body.split("\n")
+                  if l.strip() and not l.strip().startswith((";", ".")) and not l.strip().endswith(":")]
+        for k, l in enumerate(instrs):
+            m = re.match(r"v_mfma\S+ a\[(\d+):(\d+)\]", l)
+            if not m:
+                continue
+            lo, hi = int(m.group(1)), int(m.group(2))
+            for q in instrs[max(0, k - 6):k]:
+                w = re.match(r"v_accvgpr_write_b32 a(\d+),", q)
+                if w and lo <= int(w.group(1)) <= hi:
+                    findings.append(f"{nm}: v_accvgpr_write a{w.group(1)} within six instructions of '{l[:60]}'")
+        for off, base in re.findall(r"global_load_lds_dwordx4 (\S+) (\S+)", body):
+            if not base.startswith("s["):
+                findings.append(f"{nm}: LDS copy with a vector base address ({off} {base})")
+        n_acc = 128 if ("ELi4ELi1ELi4E" in nm or "shortk" in nm) else 64
+        if body.count("v_accvgpr_mov") > n_acc:
+            findings.append(f"{nm}: {body.count('v_accvgpr_mov')} v_accvgpr_mov (accumulators copied around MFMAs)")
+        tail = text[end:end + 8000]
+        sc = re.search(r"; ScratchSize: (\d+)", tail)
+        if sc and int(sc.group(1)) > 0 and nm.endswith("Li0EEEvNS0_8GemmArgsE") and "shortk" not in nm:
+            findings.append(f"{nm}: {sc.group(1)} bytes of scratch per lane")
+        if sc and int(sc.group(1)) > 0 and "shortk" in nm:
+            findings.append(f"{nm}: {sc.group(1)} bytes of scratch per lane")
+    return names, findings
+
+
 if __name__ == "__main__":
+    if "--check-asm" in sys.argv:
+        kernels, found = check_asm()
+        print(f"{len(kernels)} kernels scanned")
+        for f in found:
+            print("FINDING:", f)
+        sys.exit(1 if found else 0)
     print(build(force="--force" in sys.argv))
