@@ -27,9 +27,14 @@
  *    subnormals kept.
  *
  * Scale groups.  A tensor is a batch of matrices [batch][rows][cols].  Matrix b
- * belongs to batch group g = b % batch_groups (batch_groups = 1: one group for
- * the whole batch, "tensor"/"channel" level; batch_groups = H with the batch
- * laid out [example][head]: one group per head, shared by the examples).  With
+ * belongs to batch group g = (b / batch_inner) % batch_groups (batch_groups = 1:
+ * one group for the whole batch, "tensor"/"channel" level; batch_groups = H with
+ * the batch laid out [example][head]: one group per head, shared by the
+ * examples -- the fine-grained level of the Results section, which adds batch
+ * dimensions other than the examples' to the scale's index).  With the batch
+ * laid out [outer][mid][inner], batch_groups = mid and batch_inner = inner give
+ * one group per index of the middle dimensions, shared over outer and inner:
+ * any run of neighbouring batch dimensions can carry the scales.  With
  * per_channel = 1 every index c of the non-contracting axis has its own step
  * size, shared by the matrices of the group: delta[g * C + c], C = extent of
  * the non-contracting axis.  With per_channel = 0: delta[g].
@@ -76,8 +81,8 @@ typedef struct {
 
 typedef struct {
     int32_t per_channel;     /* 0: one step size per batch group; 1: one per non-contracting index */
-    int32_t reserved;        /* must be 0 */
-    int64_t batch_groups;    /* >= 1 and dividing nothing in particular: group = b % batch_groups  */
+    int32_t batch_inner;     /* >= 0; 0 means 1: consecutive matrices that share a group            */
+    int64_t batch_groups;    /* >= 1: group = (b / batch_inner) % batch_groups                      */
 } qmm_granularity;
 
 /* Number of step sizes qmm_scale writes / qmm_quantize reads for this tensor. */
@@ -187,7 +192,7 @@ qmm_status qmm_metric(const void* y, qmm_dtype y_dtype, const float* y_ref, cons
 /*
  * qmm_dequantize -- the reduced-precision value of every quantized element (the v-tilde of Eq. 2), for looking at
  * the quantization error of a tensor itself rather than of a product:
- *     out[b][r][k] = fl32( value(codes[b][r][k]) * delta[(b % batch_groups) * C + (per_channel ? r : 0)] )
+ *     out[b][r][k] = fl32( value(codes[b][r][k]) * delta[group(b) * C + (per_channel ? r : 0)] )
  * with codes and delta exactly as qmm_quantize takes / writes them (C = rows if per_channel, else 1); the code's
  * value is exact in binary32, so this is one rounding; bfloat16 output rounds that once more (RNE).
  * An FP8 NaN code gives NaN, an E5M2 infinity code gives infinity, the INT8 code 0x80 gives -128 delta.

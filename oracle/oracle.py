@@ -53,9 +53,9 @@ def lib():
         L.orc_sr_bits.restype = u32; L.orc_sr_bits.argtypes = [u64, u64]
         L.orc_bf16_round.restype = f32; L.orc_bf16_round.argtypes = [f32]
         L.orc_scale.restype = None
-        L.orc_scale.argtypes = [vp, i64, i64, i64, i32, i32, i32, i64, vp]
+        L.orc_scale.argtypes = [vp, i64, i64, i64, i32, i32, i32, i64, i64, vp]
         L.orc_quantize.restype = None
-        L.orc_quantize.argtypes = [vp, i64, i64, i64, i32, i32, i32, i64, vp, i32, u64, u64, vp]
+        L.orc_quantize.argtypes = [vp, i64, i64, i64, i32, i32, i32, i64, i64, vp, i32, u64, u64, vp]
         L.orc_gemm_codes.restype = None
         L.orc_gemm_codes.argtypes = [vp, i32, vp, i32, i64, i64, i64, i64, vp, vp]
         L.orc_gemm_codes_rows.restype = None
@@ -63,13 +63,13 @@ def lib():
         L.orc_gemm_int8.restype = i64
         L.orc_gemm_int8.argtypes = [vp, vp, i64, i64, i64, i64, vp]
         L.orc_dequant.restype = None
-        L.orc_dequant.argtypes = [vp, i64, i64, i64, vp, i32, i64, vp, i32, i64, i32, vp]
+        L.orc_dequant.argtypes = [vp, i64, i64, i64, vp, i32, i64, i64, vp, i32, i64, i64, i32, vp]
         L.orc_ref_gemm.restype = None
         L.orc_ref_gemm.argtypes = [vp, vp, i64, i64, i64, i64, vp]
         L.orc_metric.restype = None
         L.orc_metric.argtypes = [vp, vp, vp, i64, vp]
         L.orc_dequantize_codes.restype = None
-        L.orc_dequantize_codes.argtypes = [vp, i64, i64, i64, i32, i32, i64, vp, vp]
+        L.orc_dequantize_codes.argtypes = [vp, i64, i64, i64, i32, i32, i64, i64, vp, vp]
         L.orc_moments.restype = None
         L.orc_moments.argtypes = [vp, i64, vp]
         _lib = L
@@ -148,22 +148,22 @@ def n_scales(shape3, contract_axis, per_channel, batch_groups):
     return batch_groups * c
 
 
-def scale(x, contract_axis, fmt, per_channel=False, batch_groups=1):
+def scale(x, contract_axis, fmt, per_channel=False, batch_groups=1, batch_inner=1):
     x = _f32_3d(x)
     b, r, c = x.shape
     delta = np.empty(n_scales(x.shape, contract_axis, per_channel, batch_groups), dtype=np.float32)
-    lib().orc_scale(_p(x), b, r, c, contract_axis, fmt, int(per_channel), batch_groups, _p(delta))
+    lib().orc_scale(_p(x), b, r, c, contract_axis, fmt, int(per_channel), batch_groups, batch_inner, _p(delta))
     return delta
 
 
-def quantize(x, contract_axis, fmt, delta, per_channel=False, batch_groups=1, mode=RTNE, seed=0, offset=0):
+def quantize(x, contract_axis, fmt, delta, per_channel=False, batch_groups=1, mode=RTNE, seed=0, offset=0, batch_inner=1):
     x = _f32_3d(x)
     b, r, c = x.shape
     delta = np.ascontiguousarray(delta, dtype=np.float32)
     assert delta.size == n_scales(x.shape, contract_axis, per_channel, batch_groups)
     nc, kc = (r, c) if contract_axis == 1 else (c, r)
     codes = np.empty((b, nc, kc), dtype=np.uint8)
-    lib().orc_quantize(_p(x), b, r, c, contract_axis, fmt, int(per_channel), batch_groups, _p(delta),
+    lib().orc_quantize(_p(x), b, r, c, contract_axis, fmt, int(per_channel), batch_groups, batch_inner, _p(delta),
                        mode, int(seed), int(offset), _p(codes))
     return codes
 
@@ -204,7 +204,8 @@ def gemm_int8(a, b):
     return acc
 
 
-def dequant(acc, dl, dr, l_per_channel=False, l_groups=1, r_per_channel=False, r_groups=1, out_bf16=False):
+def dequant(acc, dl, dr, l_per_channel=False, l_groups=1, r_per_channel=False, r_groups=1, out_bf16=False,
+            l_inner=1, r_inner=1):
     acc = np.ascontiguousarray(acc, dtype=np.float64)
     if acc.ndim == 2:
         acc = acc[None]
@@ -213,8 +214,8 @@ def dequant(acc, dl, dr, l_per_channel=False, l_groups=1, r_per_channel=False, r
     assert dl.size == l_groups * (m if l_per_channel else 1)
     assert dr.size == r_groups * (n if r_per_channel else 1)
     y = np.empty((bt, m, n), dtype=np.float32)
-    lib().orc_dequant(_p(acc), bt, m, n, _p(dl), int(l_per_channel), l_groups, _p(dr), int(r_per_channel),
-                      r_groups, int(out_bf16), _p(y))
+    lib().orc_dequant(_p(acc), bt, m, n, _p(dl), int(l_per_channel), l_groups, l_inner, _p(dr), int(r_per_channel),
+                      r_groups, r_inner, int(out_bf16), _p(y))
     return y
 
 
@@ -240,7 +241,7 @@ def metric(y, r, d=None):
     return out
 
 
-def dequantize_codes(codes, fmt, delta, per_channel=False, batch_groups=1):
+def dequantize_codes(codes, fmt, delta, per_channel=False, batch_groups=1, batch_inner=1):
     """Values (float32) of codes [batch, nc, kc] (or [nc, kc]) as laid out by quantize: code value times step size."""
     codes = np.ascontiguousarray(codes, dtype=np.uint8)
     shape = codes.shape
@@ -250,7 +251,7 @@ def dequantize_codes(codes, fmt, delta, per_channel=False, batch_groups=1):
     delta = np.ascontiguousarray(delta, dtype=np.float32)
     assert delta.size == batch_groups * (nc if per_channel else 1)
     out = np.empty(codes.shape, dtype=np.float32)
-    lib().orc_dequantize_codes(_p(codes), b, nc, kc, fmt, int(per_channel), batch_groups, _p(delta), _p(out))
+    lib().orc_dequantize_codes(_p(codes), b, nc, kc, fmt, int(per_channel), batch_groups, batch_inner, _p(delta), _p(out))
     return out.reshape(shape)
 
 

@@ -13,9 +13,12 @@
  * [batch][rows][cols]; a bfloat16 input is widened to binary32 by the caller
  * (that widening is exact).  "contract_axis" names the axis that the matrix
  * multiply sums over (0 = rows, 1 = cols).  Codes are written
- * [batch][non-contracting][contracting].  Scale groups: group g = b %
- * batch_groups; with per_channel there is one step size for every index of
- * the non-contracting axis, delta[g*C + c]; otherwise one per group, delta[g].
+ * [batch][non-contracting][contracting].  Scale groups: group g = (b /
+ * batch_inner) % batch_groups (the Results section's granularity levels: one
+ * group for the whole batch, or one per index of some of the batch dimensions;
+ * with the batch laid out [outer][mid][inner] the groups follow mid); with
+ * per_channel there is one step size for every index of the non-contracting
+ * axis, delta[g*C + c]; otherwise one per group, delta[g].
  *
  * Parity pins (tests/test_oracle_*.py): closed-form value tables and the three
  * printed maxima; brute-force nearest-value search written separately in
@@ -245,8 +248,13 @@ static int64_t n_channels(int64_t rows, int64_t cols, int contract_axis, int per
  * one correctly rounded division; the maximum is taken over magnitude bit
  * patterns so an inf or NaN element dominates; an all-zero group gets
  * delta = 1; a quotient below 2^-126 is raised to 2^-126. */
+static int64_t group_of(int64_t b, int64_t batch_groups, int64_t batch_inner)
+{
+    return (b / (batch_inner > 0 ? batch_inner : 1)) % batch_groups;
+}
+
 void orc_scale(const float* x, int64_t batch, int64_t rows, int64_t cols, int contract_axis,
-               int fmt, int per_channel, int64_t batch_groups, float* delta)
+               int fmt, int per_channel, int64_t batch_groups, int64_t batch_inner, float* delta)
 {
     int64_t C = n_channels(rows, cols, contract_axis, per_channel);
     int64_t ng = batch_groups * C;
@@ -258,7 +266,7 @@ void orc_scale(const float* x, int64_t batch, int64_t rows, int64_t cols, int co
                 uint32_t bits; memcpy(&bits, &v, 4);
                 bits &= 0x7FFFFFFFu;
                 int64_t ch = per_channel ? (contract_axis == 1 ? r : c) : 0;
-                int64_t g = (b % batch_groups) * C + ch;
+                int64_t g = group_of(b, batch_groups, batch_inner) * C + ch;
                 if (bits > amax[g]) amax[g] = bits;
             }
     float qmax = (float)orc_qmax(fmt);
@@ -284,7 +292,7 @@ void orc_scale(const float* x, int64_t batch, int64_t rows, int64_t cols, int co
  * rounded reciprocal per group and one correctly rounded product per element.
  * Output order [batch][non-contracting][contracting]. */
 void orc_quantize(const float* x, int64_t batch, int64_t rows, int64_t cols, int contract_axis,
-                  int fmt, int per_channel, int64_t batch_groups, const float* delta,
+                  int fmt, int per_channel, int64_t batch_groups, int64_t batch_inner, const float* delta,
                   int mode, uint64_t seed, uint64_t offset, uint8_t* codes)
 {
     int64_t NC = contract_axis == 1 ? rows : cols;   /* non-contracting extent */
@@ -292,7 +300,7 @@ void orc_quantize(const float* x, int64_t batch, int64_t rows, int64_t cols, int
     int64_t C = n_channels(rows, cols, contract_axis, per_channel);
     for (int64_t b = 0; b < batch; ++b)
         for (int64_t n = 0; n < NC; ++n) {
-            float d = delta[(b % batch_groups) * C + (per_channel ? n : 0)];
+            float d = delta[group_of(b, batch_groups, batch_inner) * C + (per_channel ? n : 0)];
             volatile float rho = 1.0f / d;
             for (int64_t k = 0; k < KC; ++k) {
                 int64_t r = contract_axis == 1 ? n : k;
@@ -399,15 +407,15 @@ float orc_bf16_round(float v)
  * indexed by the row of the left operand, deltaR by the row of the right
  * operand (= output column) when per-channel; both by b % groups. */
 void orc_dequant(const double* acc, int64_t batch, int64_t M, int64_t N,
-                 const float* dl, int l_per_channel, int64_t l_groups,
-                 const float* dr, int r_per_channel, int64_t r_groups,
+                 const float* dl, int l_per_channel, int64_t l_groups, int64_t l_inner,
+                 const float* dr, int r_per_channel, int64_t r_groups, int64_t r_inner,
                  int out_bf16, float* y)
 {
     for (int64_t b = 0; b < batch; ++b)
         for (int64_t i = 0; i < M; ++i)
             for (int64_t j = 0; j < N; ++j) {
-                float sl = dl[(b % l_groups) * (l_per_channel ? M : 1) + (l_per_channel ? i : 0)];
-                float sr = dr[(b % r_groups) * (r_per_channel ? N : 1) + (r_per_channel ? j : 0)];
+                float sl = dl[group_of(b, l_groups, l_inner) * (l_per_channel ? M : 1) + (l_per_channel ? i : 0)];
+                float sr = dr[group_of(b, r_groups, r_inner) * (r_per_channel ? N : 1) + (r_per_channel ? j : 0)];
                 volatile float a = (float)acc[(b * M + i) * N + j];
                 volatile float t = a * sl;
                 volatile float v = t * sr;
@@ -523,12 +531,12 @@ void orc_moments(const float* x, int64_t n, double* out)
  * delta[(b % groups) * C + (per_channel ? row : 0)].  An FP8 NaN code gives NaN; the INT8 code 0x80, which the
  * encoder never produces, gives -128 delta. */
 void orc_dequantize_codes(const uint8_t* codes, int64_t batch, int64_t nc, int64_t kc, int fmt,
-                          int per_channel, int64_t groups, const float* delta, float* out)
+                          int per_channel, int64_t groups, int64_t inner, const float* delta, float* out)
 {
     const int64_t C = per_channel ? nc : 1;
     for (int64_t b = 0; b < batch; ++b)
         for (int64_t r = 0; r < nc; ++r) {
-            const float d = delta[(b % groups) * C + (per_channel ? r : 0)];
+            const float d = delta[group_of(b, groups, inner) * C + (per_channel ? r : 0)];
             for (int64_t k = 0; k < kc; ++k) {
                 const int64_t i = (b * nc + r) * kc + k;
                 out[i] = (float)orc_code_value(fmt, codes[i]) * d;

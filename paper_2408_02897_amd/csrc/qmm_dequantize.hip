@@ -35,7 +35,7 @@ template <int FMT> QMM_DEV float decode(uint32_t code)
 struct DArgs {
     const uint8_t* codes; const float* delta; void* out;
     int64_t rows, K, total_rows;      // total_rows = batch * rows
-    int64_t groups; int per_channel; int out_bf16;
+    int64_t groups; int64_t inner; int per_channel; int out_bf16;
 };
 
 // One thread per 16 consecutive codes of a row (K % 16 == 0), grid-stride.
@@ -48,7 +48,7 @@ dequantize_vec(DArgs a)
     for (int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x; v < nvec; v += stride) {
         const int64_t row = v / vec_per_row;                       // b * rows + r
         const int64_t b = row / a.rows, r = row - b * a.rows;
-        const float d = a.delta[(b % a.groups) * (a.per_channel ? a.rows : 1) + (a.per_channel ? r : 0)];
+        const float d = a.delta[((b / a.inner) % a.groups) * (a.per_channel ? a.rows : 1) + (a.per_channel ? r : 0)];
         const u32x4 w = reinterpret_cast<const u32x4*>(a.codes)[v];
         float y[16];
 #pragma unroll
@@ -79,7 +79,7 @@ dequantize_generic(DArgs a)
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
         const int64_t row = i / a.K;
         const int64_t b = row / a.rows, r = row - b * a.rows;
-        const float d = a.delta[(b % a.groups) * (a.per_channel ? a.rows : 1) + (a.per_channel ? r : 0)];
+        const float d = a.delta[((b / a.inner) % a.groups) * (a.per_channel ? a.rows : 1) + (a.per_channel ? r : 0)];
         const float y = decode<FMT>(a.codes[i]) * d;
         if (a.out_bf16) static_cast<__bf16*>(a.out)[i] = (__bf16)y;
         else static_cast<float*>(a.out)[i] = y;
@@ -110,12 +110,13 @@ extern "C" qmm_status qmm_dequantize(const uint8_t* codes, int64_t batch, int64_
     if (!g) return QMM_ERR_NULL;
     if (fmt != QMM_FMT_INT8 && fmt != QMM_FMT_E4M3 && fmt != QMM_FMT_E5M2) return QMM_ERR_ENUM;
     if (out_dtype != QMM_DT_BF16 && out_dtype != QMM_DT_F32) return QMM_ERR_ENUM;
-    if (g->batch_groups < 1 || g->reserved != 0 || (g->per_channel != 0 && g->per_channel != 1)) return QMM_ERR_ENUM;
+    if (g->batch_groups < 1 || g->batch_inner < 0 || (g->per_channel != 0 && g->per_channel != 1)) return QMM_ERR_ENUM;
     if (batch < 0 || rows < 0 || K < 0) return QMM_ERR_SHAPE;
     if (batch * rows * K == 0) return QMM_OK;
     if (!codes || !delta || !out) return QMM_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(out) & (out_dtype == QMM_DT_BF16 ? 1u : 3u)) return QMM_ERR_ALIGN;
-    DArgs a{codes, delta, out, rows, K, batch * rows, g->batch_groups, g->per_channel, out_dtype == QMM_DT_BF16};
+    DArgs a{codes, delta, out, rows, K, batch * rows, g->batch_groups, g->batch_inner > 0 ? g->batch_inner : 1,
+            g->per_channel, out_dtype == QMM_DT_BF16};
     hipStream_t s = as_stream(stream);
     if (fmt == QMM_FMT_INT8) return launch<QMM_FMT_INT8>(a, s);
     if (fmt == QMM_FMT_E4M3) return launch<QMM_FMT_E4M3>(a, s);

@@ -64,6 +64,7 @@ struct GemmArgs {
     int64_t batch;
     const float* da; const float* db;
     int64_t da_groups, db_groups;     // batch groups
+    int64_t da_inner, db_inner;       // consecutive matrices sharing a group: group = (b / inner) % groups
     int da_per_channel, db_per_channel;
     void* y; int y_bf16;              // may be null
     void* acc_out;                    // may be null
@@ -263,10 +264,10 @@ gemm_kernel(GemmArgs g)
             float d;
             if (is_a) {
                 int64_t row = m0 + p; row = row < g.M ? row : g.M - 1;
-                d = g.da[(bidx % g.da_groups) * (g.da_per_channel ? g.M : 1) + (g.da_per_channel ? row : 0)];
+                d = g.da[((bidx / g.da_inner) % g.da_groups) * (g.da_per_channel ? g.M : 1) + (g.da_per_channel ? row : 0)];
             } else {
                 int64_t row = n0 + WN * (p / WN) + TILES_N * (p % R) + (p / R) % TILES_N; row = row < g.N ? row : g.N - 1;
-                d = g.db[(bidx % g.db_groups) * (g.db_per_channel ? g.N : 1) + (g.db_per_channel ? row : 0)];
+                d = g.db[((bidx / g.db_inner) % g.db_groups) * (g.db_per_channel ? g.N : 1) + (g.db_per_channel ? row : 0)];
             }
             f_rho[f] = 1.0f / d;
         }
@@ -538,8 +539,8 @@ gemm_kernel(GemmArgs g)
     //  so for a fixed register the TILES_N accumulators of a lane are consecutive columns, and the lanes of a
     //  store instruction cover whole rows of the wavefront tile.
     const int64_t m_base = m0 + wm * WM, n_base = n0 + wn * WN;
-    const float* da = g.da ? g.da + (bidx % g.da_groups) * (g.da_per_channel ? g.M : 1) : nullptr;
-    const float* db = g.db ? g.db + (bidx % g.db_groups) * (g.db_per_channel ? g.N : 1) : nullptr;
+    const float* da = g.da ? g.da + ((bidx / g.da_inner) % g.da_groups) * (g.da_per_channel ? g.M : 1) : nullptr;
+    const float* db = g.db ? g.db + ((bidx / g.db_inner) % g.db_groups) * (g.db_per_channel ? g.N : 1) : nullptr;
     constexpr bool descale = (KIND != KIND_BF16);
     constexpr int REGS = F8 ? 4 : 16;
     const int64_t n = n_base + TILES_N * (lane & (R - 1));     // first of this lane's TILES_N columns
@@ -895,8 +896,8 @@ gemm_shortk_kernel(GemmArgs g)
         {
             const int64_t bidx = cur.bidx;
             const int64_t m_base = cur.m0 + wm * WM, n_base = cur.n0 + wn * WN;
-            const float* da = g.da ? g.da + (bidx % g.da_groups) * (g.da_per_channel ? g.M : 1) : nullptr;
-            const float* db = g.db ? g.db + (bidx % g.db_groups) * (g.db_per_channel ? g.N : 1) : nullptr;
+            const float* da = g.da ? g.da + ((bidx / g.da_inner) % g.da_groups) * (g.da_per_channel ? g.M : 1) : nullptr;
+            const float* db = g.db ? g.db + ((bidx / g.db_inner) % g.db_groups) * (g.db_per_channel ? g.N : 1) : nullptr;
             int lane_e = lane;                    // kept out of the loop-invariant code the compiler would hoist
             asm volatile("" : "+v"(lane_e));
             const int64_t n = n_base + TILES_N * (lane_e & (R - 1));
@@ -1085,8 +1086,8 @@ gemm_direct_kernel(GemmArgs g)
     }
 
     // ---- epilogue: (acc * deltaA[row]) * deltaB[column], in that order
-    const float* da = g.da ? g.da + (bidx % g.da_groups) * (g.da_per_channel ? g.M : 1) : nullptr;
-    const float* db = g.db ? g.db + (bidx % g.db_groups) * (g.db_per_channel ? g.N : 1) : nullptr;
+    const float* da = g.da ? g.da + ((bidx / g.da_inner) % g.da_groups) * (g.da_per_channel ? g.M : 1) : nullptr;
+    const float* db = g.db ? g.db + ((bidx / g.db_inner) % g.db_groups) * (g.db_per_channel ? g.N : 1) : nullptr;
     constexpr bool descale = (KIND != KIND_BF16);
     const int64_t n = n_base + TILES_N * (lane & (R - 1));
     const int lane_row = F8 ? 4 * (lane >> 4) : 4 * (lane >> 5);
@@ -1211,7 +1212,7 @@ splitk_reduce(GemmArgs g)
         }
     }
     float sl = 1.0f;
-    if constexpr (KIND != KIND_BF16) sl = g.da[(bidx % g.da_groups) * (g.da_per_channel ? g.M : 1) + (g.da_per_channel ? m : 0)];
+    if constexpr (KIND != KIND_BF16) sl = g.da[((bidx / g.da_inner) % g.da_groups) * (g.da_per_channel ? g.M : 1) + (g.da_per_channel ? m : 0)];
     for (int e = 0; e < 4; ++e) {
         if (n + e >= g.N) break;
         float a;
@@ -1219,7 +1220,7 @@ splitk_reduce(GemmArgs g)
         if constexpr (KIND == KIND_I8) { raw = (uint32_t)si[e]; a = (float)si[e]; }
         else { raw = __float_as_uint(sf[e]); a = sf[e]; }
         if constexpr (KIND != KIND_BF16) {
-            const float sr = g.db[(bidx % g.db_groups) * (g.db_per_channel ? g.N : 1) + (g.db_per_channel ? n + e : 0)];
+            const float sr = g.db[((bidx / g.db_inner) % g.db_groups) * (g.db_per_channel ? g.N : 1) + (g.db_per_channel ? n + e : 0)];
             a = (a * sl) * sr;
         }
         const int64_t o = row * g.N + n + e;
@@ -1361,7 +1362,7 @@ qmm_status check_operand(const qmm_operand* o)
     if (!is8(o->format) && o->format != QMM_FMT_BF16) return QMM_ERR_ENUM;
     if (o->is_codes != 0 && o->is_codes != 1) return QMM_ERR_ENUM;
     if (o->format == QMM_FMT_BF16 && o->is_codes) return QMM_ERR_ENUM;
-    if (o->gran.batch_groups < 1 || o->gran.reserved != 0 || (o->gran.per_channel != 0 && o->gran.per_channel != 1))
+    if (o->gran.batch_groups < 1 || o->gran.batch_inner < 0 || (o->gran.per_channel != 0 && o->gran.per_channel != 1))
         return QMM_ERR_ENUM;
     return QMM_OK;
 }
@@ -1410,6 +1411,8 @@ extern "C" qmm_status qmm_gemm(const qmm_operand* a, const qmm_operand* b, int64
     g.M = M; g.N = N; g.rowbytes = K * esz; g.batch = batch;
     g.da = bf ? nullptr : a->delta; g.db = bf ? nullptr : b->delta;
     g.da_groups = a->gran.batch_groups; g.db_groups = b->gran.batch_groups;
+    g.da_inner = a->gran.batch_inner > 0 ? a->gran.batch_inner : 1;
+    g.db_inner = b->gran.batch_inner > 0 ? b->gran.batch_inner : 1;
     g.da_per_channel = a->gran.per_channel; g.db_per_channel = b->gran.per_channel;
     g.y = y; g.y_bf16 = y_dtype == QMM_DT_BF16; g.acc_out = acc_out;
     g.splits = plan_splits(M, N, g.rowbytes, batch, fuse);

@@ -19,6 +19,7 @@ struct QArgs {
     uint8_t* codes;
     int64_t batch, rows, cols, batch_stride, row_stride;
     int64_t groups;        // batch groups
+    int64_t inner;         // consecutive matrices sharing a group: group = (b / inner) % groups
     int64_t channels;      // step sizes per group (1 when not per-channel)
     uint64_t seed, offset;
 };
@@ -37,7 +38,7 @@ quantize_rows_bf16x16(QArgs a)
     if (v >= vpr * a.rows) return;
     const int64_t b = blockIdx.y;
     const int64_t r = v / vpr, cv = v - r * vpr;
-    const float d = a.delta[(b % a.groups) * a.channels + (a.channels > 1 ? r : 0)];
+    const float d = a.delta[((b / a.inner) % a.groups) * a.channels + (a.channels > 1 ? r : 0)];
     const float rho = 1.0f / d;
     const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.x) + b * a.batch_stride +
                                                       r * a.row_stride + cv * 16);
@@ -77,7 +78,7 @@ quantize_generic(QArgs a, int contract_axis)
     const int64_t b = blockIdx.y;
     const int64_t n = i / KC, k = i - n * KC;
     const int64_t r = contract_axis == 1 ? n : k, c = contract_axis == 1 ? k : n;
-    const float d = a.delta[(b % a.groups) * a.channels + (a.channels > 1 ? n : 0)];
+    const float d = a.delta[((b / a.inner) % a.groups) * a.channels + (a.channels > 1 ? n : 0)];
     const float rho = 1.0f / d;
     const float t = load_f32<T>(static_cast<const T*>(a.x) + b * a.batch_stride + r * a.row_stride + c) * rho;
     const int64_t p = (b * NC + n) * KC + k;
@@ -111,7 +112,7 @@ quantize_cols_bf16(QArgs a)
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const int64_t nn = n + j < N ? n + j : N - 1;
-        rho[j] = 1.0f / a.delta[(b % a.groups) * a.channels + (a.channels > 1 ? nn : 0)];
+        rho[j] = 1.0f / a.delta[((b / a.inner) % a.groups) * a.channels + (a.channels > 1 ? nn : 0)];
     }
     uint32_t lo[8] = {}, hi[8] = {};
     SrStream sr(a.seed);
@@ -194,7 +195,7 @@ extern "C" qmm_status qmm_quantize(const qmm_tensor* x, qmm_format fmt, const qm
     if (x->contract_axis != 0 && x->contract_axis != 1) return QMM_ERR_ENUM;
     if (fmt != QMM_FMT_INT8 && fmt != QMM_FMT_E4M3 && fmt != QMM_FMT_E5M2) return QMM_ERR_ENUM;
     if (mode != QMM_ROUND_RTNE && mode != QMM_ROUND_STOCHASTIC) return QMM_ERR_ENUM;
-    if (g->batch_groups < 1 || g->reserved != 0 || (g->per_channel != 0 && g->per_channel != 1)) return QMM_ERR_ENUM;
+    if (g->batch_groups < 1 || g->batch_inner < 0 || (g->per_channel != 0 && g->per_channel != 1)) return QMM_ERR_ENUM;
     if (x->batch < 0 || x->rows < 0 || x->cols < 0 || x->row_stride < x->cols) return QMM_ERR_SHAPE;
     if (x->batch > 1 && x->rows > 0 && x->batch_stride < (x->rows - 1) * x->row_stride + x->cols) return QMM_ERR_SHAPE;
     if (x->batch > 65535) return QMM_ERR_UNSUPPORTED;
@@ -206,6 +207,7 @@ extern "C" qmm_status qmm_quantize(const qmm_tensor* x, qmm_format fmt, const qm
     a.batch = x->batch; a.rows = x->rows; a.cols = x->cols;
     a.batch_stride = x->batch_stride; a.row_stride = x->row_stride;
     a.groups = g->batch_groups;
+    a.inner = g->batch_inner > 0 ? g->batch_inner : 1;
     a.channels = g->per_channel ? (x->contract_axis == 1 ? x->rows : x->cols) : 1;
     a.seed = seed; a.offset = offset;
     hipStream_t s = as_stream(stream);

@@ -158,15 +158,16 @@ absmax_cols_generic(const T* __restrict__ x, int64_t batch_stride, int64_t row_s
     partial[((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * cols + c] = m;
 }
 
-// Fold partial[b][P][C] over b == g (mod G) and over p, then delta = absmax / qmax.
+// Fold partial[b][P][C] over the matrices b of group g, (b / inner) % G == g, and over p; then delta = absmax / qmax.
+// The matrices of a group: b = q * inner + i for q = g, g + G, ... and i = 0 .. inner - 1.
 // C == 1: one workgroup per group.  C > 1: one thread per (g, c).
 __global__ void __launch_bounds__(kThreads)
-finalize_single(const uint32_t* __restrict__ partial, int64_t batch, int64_t P, int64_t G, float qmax,
+finalize_single(const uint32_t* __restrict__ partial, int64_t batch, int64_t P, int64_t G, int64_t inner, float qmax,
                 float* __restrict__ delta)
 {
     const int64_t g = blockIdx.x;
     uint32_t m = 0;
-    if (batch <= G && P <= 4 * kThreads) {
+    if (inner == 1 && batch <= G && P <= 4 * kThreads) {
         // one matrix per group and few partials: request them all before folding
         uint32_t v[4];
 #pragma unroll
@@ -176,16 +177,17 @@ finalize_single(const uint32_t* __restrict__ partial, int64_t batch, int64_t P, 
         }
         m = max(max(v[0], v[1]), max(v[2], v[3]));
     } else {
-        for (int64_t b = g; b < batch; b += G)
-            for (int64_t p = threadIdx.x; p < P; p += kThreads) m = max(m, partial[b * P + p]);
+        for (int64_t q = g; q * inner < batch; q += G)
+            for (int64_t b = q * inner; b < min(batch, (q + 1) * inner); ++b)
+                for (int64_t p = threadIdx.x; p < P; p += kThreads) m = max(m, partial[b * P + p]);
     }
     m = block_max_u32(m);
     if (threadIdx.x == 0) delta[g] = delta_from_absmax_bits(m, qmax);
 }
 // Workgroup = 32 channels x 8 lanes over the (matrix, partial) pairs of the group; max is order-free.
 __global__ void __launch_bounds__(kThreads)
-finalize_channels(const uint32_t* __restrict__ partial, int64_t batch, int64_t P, int64_t C, int64_t G, float qmax,
-                  float* __restrict__ delta)
+finalize_channels(const uint32_t* __restrict__ partial, int64_t batch, int64_t P, int64_t C, int64_t G, int64_t inner,
+                  float qmax, float* __restrict__ delta)
 {
     __shared__ uint32_t s[8][32];
     const int cl = threadIdx.x & 31, pl = threadIdx.x >> 5;
@@ -193,7 +195,8 @@ finalize_channels(const uint32_t* __restrict__ partial, int64_t batch, int64_t P
     const int64_t g = blockIdx.y;
     uint32_t m = 0;
     if (c < C) {
-        for (int64_t b = g; b < batch; b += G) {
+        for (int64_t q = g; q * inner < batch; q += G)
+        for (int64_t b = q * inner; b < min(batch, (q + 1) * inner); ++b) {
             const uint32_t* base = partial + b * P * C + c;
             int64_t p = pl;
             for (; p + 24 < P; p += 32) {      // four loads in flight
@@ -293,7 +296,7 @@ extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_g
     if (!g || !delta_out) return QMM_ERR_NULL;
     if (!valid_tensor(x, &st)) return st;
     if (fmt != QMM_FMT_INT8 && fmt != QMM_FMT_E4M3 && fmt != QMM_FMT_E5M2) return QMM_ERR_ENUM;
-    if (g->batch_groups < 1 || g->reserved != 0 || (g->per_channel != 0 && g->per_channel != 1)) return QMM_ERR_ENUM;
+    if (g->batch_groups < 1 || g->batch_inner < 0 || (g->per_channel != 0 && g->per_channel != 1)) return QMM_ERR_ENUM;
     const int64_t nscales = qmm_num_scales(x, g);
     if (nscales == 0) return QMM_OK;
     if (x->batch * x->rows * x->cols > 0 && !x->data) return QMM_ERR_NULL;
@@ -347,11 +350,11 @@ extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_g
     // An empty tensor has no partials: fold over zero matrices so every group gets delta = 1.
     const int64_t fold_batch = nelem > 0 ? x->batch : 0;
     if (nelem == 0) P = 0;
-    const int64_t G = g->batch_groups;
+    const int64_t G = g->batch_groups, inner = g->batch_inner > 0 ? g->batch_inner : 1;
     if (C == 1)
-        finalize_single<<<(unsigned)G, kThreads, 0, s>>>(partial, fold_batch, P, G, qmax, delta_out);
+        finalize_single<<<(unsigned)G, kThreads, 0, s>>>(partial, fold_batch, P, G, inner, qmax, delta_out);
     else
         finalize_channels<<<dim3((unsigned)((C + 31) / 32), (unsigned)G), kThreads, 0, s>>>(
-            partial, fold_batch, P, C, G, qmax, delta_out);
+            partial, fold_batch, P, C, G, inner, qmax, delta_out);
     return launch_status();
 }

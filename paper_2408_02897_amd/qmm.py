@@ -30,7 +30,7 @@ class Tensor(ctypes.Structure):
 
 
 class Granularity(ctypes.Structure):
-    _fields_ = [("per_channel", ctypes.c_int32), ("reserved", ctypes.c_int32), ("batch_groups", ctypes.c_int64)]
+    _fields_ = [("per_channel", ctypes.c_int32), ("batch_inner", ctypes.c_int32), ("batch_groups", ctypes.c_int64)]
 
 
 class Operand(ctypes.Structure):
@@ -101,18 +101,19 @@ def tensor_desc(x, contract_axis):
     return Tensor(x.data_ptr(), _dtype_code(x), contract_axis, b, r, c, x.stride(0), x.stride(1))
 
 
-def granularity(per_channel=False, batch_groups=1):
-    return Granularity(int(per_channel), 0, int(batch_groups))
+def granularity(per_channel=False, batch_groups=1, batch_inner=1):
+    """Scale group of matrix b: (b // batch_inner) % batch_groups."""
+    return Granularity(int(per_channel), int(batch_inner), int(batch_groups))
 
 
 def _workspace(nbytes, device):
     return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
 
 
-def scale(x, contract_axis, fmt, per_channel=False, batch_groups=1, out=None, workspace=None):
+def scale(x, contract_axis, fmt, per_channel=False, batch_groups=1, out=None, workspace=None, batch_inner=1):
     """qmm_scale: step sizes (float32 device tensor of qmm_num_scales elements)."""
     L = lib()
-    t, g = tensor_desc(x, contract_axis), granularity(per_channel, batch_groups)
+    t, g = tensor_desc(x, contract_axis), granularity(per_channel, batch_groups, batch_inner)
     n = L.qmm_num_scales(ctypes.byref(t), ctypes.byref(g))
     if out is None:
         out = torch.empty(n, dtype=torch.float32, device=x.device)
@@ -124,10 +125,11 @@ def scale(x, contract_axis, fmt, per_channel=False, batch_groups=1, out=None, wo
     return out
 
 
-def quantize(x, contract_axis, fmt, delta, per_channel=False, batch_groups=1, mode=RTNE, seed=0, offset=0, out=None):
+def quantize(x, contract_axis, fmt, delta, per_channel=False, batch_groups=1, mode=RTNE, seed=0, offset=0, out=None,
+             batch_inner=1):
     """qmm_quantize: uint8 codes [batch, non-contracting, contracting]."""
     L = lib()
-    t, g = tensor_desc(x, contract_axis), granularity(per_channel, batch_groups)
+    t, g = tensor_desc(x, contract_axis), granularity(per_channel, batch_groups, batch_inner)
     nc, kc = (t.rows, t.cols) if contract_axis == 1 else (t.cols, t.rows)
     if out is None:
         out = torch.empty((t.batch, nc, kc), dtype=torch.uint8, device=x.device)
@@ -137,10 +139,10 @@ def quantize(x, contract_axis, fmt, delta, per_channel=False, batch_groups=1, mo
     return out
 
 
-def operand(data, fmt, delta=None, per_channel=False, batch_groups=1, is_codes=True):
+def operand(data, fmt, delta=None, per_channel=False, batch_groups=1, is_codes=True, batch_inner=1):
     assert data.is_contiguous()
     op = Operand(data.data_ptr(), fmt, int(is_codes), delta.data_ptr() if delta is not None else None,
-                 granularity(per_channel, batch_groups))
+                 granularity(per_channel, batch_groups, batch_inner))
     op._keep = (data, delta)   # the struct holds raw device pointers: keep their owners alive with it
     return op
 
@@ -170,11 +172,11 @@ def gemm(a, b, out_dtype=torch.float32, want_acc=False, out=None, acc_out=None, 
     return (y, acc) if want_acc else y
 
 
-def quantized_operand(x, contract_axis, fmt, per_channel=False, batch_groups=1, mode=RTNE, seed=0):
+def quantized_operand(x, contract_axis, fmt, per_channel=False, batch_groups=1, mode=RTNE, seed=0, batch_inner=1):
     """scale + quantize; returns ((codes, Operand), delta)."""
-    d = scale(x, contract_axis, fmt, per_channel, batch_groups)
-    c = quantize(x, contract_axis, fmt, d, per_channel, batch_groups, mode, seed)
-    return (c, operand(c, fmt, d, per_channel, batch_groups)), d
+    d = scale(x, contract_axis, fmt, per_channel, batch_groups, batch_inner=batch_inner)
+    c = quantize(x, contract_axis, fmt, d, per_channel, batch_groups, mode, seed, batch_inner=batch_inner)
+    return (c, operand(c, fmt, d, per_channel, batch_groups, batch_inner=batch_inner)), d
 
 
 def reference_gemm(x, w, out=None):
@@ -199,13 +201,13 @@ def metric(y, y_ref, denom=None, out=None, workspace=None):
     return out
 
 
-def dequantize(codes, fmt, delta, per_channel=False, batch_groups=1, out_dtype=torch.float32, out=None):
+def dequantize(codes, fmt, delta, per_channel=False, batch_groups=1, out_dtype=torch.float32, out=None, batch_inner=1):
     """qmm_dequantize: values of the uint8 device tensor codes [batch, rows, K] (or [rows, K])."""
     L = lib()
     assert codes.dtype == torch.uint8 and codes.is_contiguous() and codes.is_cuda
     c3 = codes if codes.dim() == 3 else codes.unsqueeze(0)
     b, r, k = c3.shape
-    g = granularity(per_channel, batch_groups)
+    g = granularity(per_channel, batch_groups, batch_inner)
     assert delta.dtype == torch.float32 and delta.numel() == batch_groups * (r if per_channel else 1)
     if out is None:
         out = torch.empty(codes.shape, dtype=out_dtype, device=codes.device)

@@ -57,6 +57,9 @@ def test_argument_errors_are_reported_before_any_launch(L):
     t4 = qmm.Tensor(fake, qmm.DT_BF16, 1, 1, 4, 16, 64, 16)
     assert L.qmm_scale(ctypes.byref(t4), qmm.E4M3, ctypes.byref(g), fake, None, 0, None) == 6
     assert L.qmm_quantize(ctypes.byref(t4), qmm.E4M3, ctypes.byref(g), fake, 5, 0, 0, fake, None) == 3
+    bad = qmm.granularity(False, 1, -1)                       # negative run length of the scale groups
+    assert L.qmm_scale(ctypes.byref(t4), qmm.E4M3, ctypes.byref(bad), fake, fake, 1024, None) == 3
+    assert L.qmm_quantize(ctypes.byref(t4), qmm.E4M3, ctypes.byref(bad), fake, 0, 0, 0, fake, None) == 3
     assert L.qmm_quantize(ctypes.byref(t4), qmm.E4M3, ctypes.byref(g), None, 0, 0, 0, fake, None) == 1
     oa = qmm.Operand(fake, qmm.E4M3, 1, fake, g); ob = qmm.Operand(fake, qmm.INT8, 1, fake, g)
     assert L.qmm_gemm(ctypes.byref(oa), ctypes.byref(ob), 1, 16, 16, 16, fake, 1, None, None, 0, None) == 5

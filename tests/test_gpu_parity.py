@@ -147,6 +147,37 @@ def test_quantize_f32_input_and_gradient_like_values():
         assert np.array_equal(got.cpu().numpy(), O.quantize(x.numpy(), 1, fmt, want_d, True, 1))
 
 
+@pytest.mark.parametrize("fmt", [qmm.INT8, qmm.E4M3])
+@pytest.mark.parametrize("per_channel", [False, True])
+@pytest.mark.parametrize("dims,groups,inner", [((2, 3, 2), 3, 2), ((3, 2, 2), 3, 4), ((2, 2, 3), 4, 3)])
+def test_scales_indexed_by_a_run_of_batch_dimensions(dims, groups, inner, per_channel, fmt):
+    """group = (b / inner) % groups through every call that takes a granularity: scale, quantize (both contracting
+    axes), the GEMM's descale and dequantize."""
+    batch = dims[0] * dims[1] * dims[2]
+    g = torch.Generator(); g.manual_seed(batch + groups)
+    x = (W.student_t((batch, 70, 96), 3, seed=31) * torch.rand(batch, 1, 1, generator=g).mul(9.9).add(0.1)).to(torch.bfloat16)
+    w = W.normal((batch, 40, 96), 0.05, seed=32)
+    for contract_axis in (1, 0):
+        d = qmm.scale(x.to(DEV), contract_axis, fmt, per_channel, groups, batch_inner=inner)
+        want_d = O.scale(np32(x), contract_axis, fmt, per_channel, groups, inner)
+        assert np.array_equal(d.cpu().numpy(), want_d)
+        c = qmm.quantize(x.to(DEV), contract_axis, fmt, d, per_channel, groups, batch_inner=inner)
+        want_c = O.quantize(np32(x), contract_axis, fmt, want_d, per_channel, groups, batch_inner=inner)
+        assert np.array_equal(c.cpu().numpy(), want_c)
+        v = qmm.dequantize(c, fmt, d, per_channel, groups, batch_inner=inner)
+        assert np.array_equal(v.cpu().numpy(), O.dequantize_codes(want_c, fmt, want_d, per_channel, groups, inner))
+    (cx, ox), dx = qmm.quantized_operand(x.to(DEV), 1, fmt, per_channel, groups, batch_inner=inner)
+    (cw, ow), dw = qmm.quantized_operand(w.to(DEV), 1, fmt, per_channel, 1)         # weights: one group for the batch
+    y, acc = qmm.gemm((cx, ox), (cw, ow), torch.float32, want_acc=True)
+    want_y = O.dequant(acc.cpu().numpy().astype(np.float64), dx.cpu().numpy(), dw.cpu().numpy(), per_channel, groups,
+                       per_channel, 1, l_inner=inner)
+    assert np.array_equal(y.cpu().numpy().view(np.uint32), want_y.view(np.uint32))
+    yb = qmm.gemm((cx, ox), (cw, ow), torch.bfloat16)
+    want_yb = O.dequant(acc.cpu().numpy().astype(np.float64), dx.cpu().numpy(), dw.cpu().numpy(), per_channel, groups,
+                        per_channel, 1, True, l_inner=inner)
+    assert np.array_equal(yb.float().cpu().numpy().view(np.uint32), want_yb.view(np.uint32))
+
+
 # ------------------------------------------------------------------------- gemm
 def _random_codes(fmt, shape, seed):
     g = torch.Generator(); g.manual_seed(seed)

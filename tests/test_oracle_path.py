@@ -70,6 +70,36 @@ def test_scale_granularity_vs_numpy(contract_axis, per_channel, groups):
     assert np.array_equal(d, want)
 
 
+@pytest.mark.parametrize("per_channel", [False, True])
+@pytest.mark.parametrize("dims,groups,inner", [((2, 3, 2), 3, 2), ((3, 4, 1), 4, 1), ((3, 2, 2), 3, 4), ((2, 2, 3), 4, 3)])
+def test_scales_indexed_by_a_run_of_batch_dimensions(dims, groups, inner, per_channel):
+    """Fine-grained level (Results): the scale's index takes in some of the batch dimensions.  Batch laid out
+    [outer][mid][inner]: groups = mid with `inner` consecutive matrices per group (cases: mid alone; the two inner
+    dimensions together; the outer dimension; the two outer dimensions together).  Step sizes against numpy maxima
+    over the complementary axes; codes and values must then use the step size of their own group."""
+    rng = np.random.default_rng(sum(dims) + groups)
+    batch = dims[0] * dims[1] * dims[2]
+    x = _bf16(rng.standard_t(3, size=(batch, 5, 8)) * rng.uniform(0.1, 10.0, (batch, 1, 1)))
+    d = O.scale(x, 1, O.E4M3, per_channel, groups, inner)
+    # matrices of group g: (b // inner) % groups == g
+    gid = (np.arange(batch) // inner) % groups
+    amax = np.stack([np.abs(x[gid == g]).max(axis=(0, 2) if per_channel else (0, 1, 2)) for g in range(groups)])
+    assert np.array_equal(d, (amax.astype(np.float32) / np.float32(448.0)).reshape(-1))
+    codes = O.quantize(x, 1, O.E4M3, d, per_channel, groups, batch_inner=inner)
+    vals = O.dequantize_codes(codes, O.E4M3, d, per_channel, groups, inner)
+    dd = d.reshape(groups, -1)
+    for b in range(batch):
+        one = O.quantize(x[b:b + 1], 1, O.E4M3, dd[gid[b]], per_channel, 1)          # that matrix alone with its group's scales
+        assert np.array_equal(codes[b], one[0])
+        assert np.array_equal(vals[b], O.dequantize_codes(one, O.E4M3, dd[gid[b]], per_channel, 1)[0])
+    acc = rng.integers(-1000, 1000, (batch, 5, 5)).astype(np.float64)
+    y = O.dequant(acc, d, d, per_channel, groups, per_channel, groups, l_inner=inner, r_inner=inner)
+    for b in range(batch):
+        sl = dd[gid[b]][:, None] if per_channel else dd[gid[b]][0]
+        sr = dd[gid[b]][None, :] if per_channel else dd[gid[b]][0]
+        assert np.array_equal(y[b], ((acc[b].astype(np.float32) * sl).astype(np.float32) * sr).astype(np.float32))
+
+
 @pytest.mark.parametrize("fmt", FMTS)
 def test_quantize_contract_axis_is_a_transpose(fmt):
     rng = np.random.default_rng(9)
