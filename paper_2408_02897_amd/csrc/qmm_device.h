@@ -167,8 +167,11 @@ QMM_DEV Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3
 #pragma unroll
     for (int round = 0; round < 10; ++round) {
         if (round > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
-        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        // one 32 x 32 -> 64 multiply per product (v_mad_u64_u32) instead of separate high and low halves: integer
+        // multiplies issue at a quarter of the plain rate and are what bounds stochastic rounding
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+        const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
         const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
         c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
     }
@@ -190,7 +193,10 @@ struct SrStream {
             cached_block = blk;
             valid = true;
         }
-        return cached.v[g & 3u] >> 8;
+        // selected by compares: indexing the four words with a run-time index would put them in scratch memory
+        const uint32_t j = (uint32_t)g & 3u;
+        const uint32_t w = j == 0 ? cached.v[0] : j == 1 ? cached.v[1] : j == 2 ? cached.v[2] : cached.v[3];
+        return w >> 8;
     }
 };
 

@@ -48,9 +48,19 @@ quantize_rows_bf16x16(QArgs a)
     if constexpr (MODE == QMM_ROUND_RTNE) {
         out = encode16_bf16_rtne<FMT>(w0, w1, rho);
     } else {
+        // element number g = p0 + e + offset draws word g % 4 of Philox block g / 4.  When the thread's first element
+        // starts a block (always, unless the caller's offset is not a multiple of 4) its 16 elements are exactly the
+        // four blocks g0/4 .. g0/4 + 3, one per output dword; otherwise the generic stream looks each element up.
+        const uint64_t g0 = (uint64_t)p0 + a.offset;
+        const bool aligned = (g0 & 3u) == 0;              // uniform over the grid
         SrStream sr(a.seed);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
+            Philox4 blk{};
+            if (aligned) {
+                const uint64_t c = (g0 >> 2) + q;
+                blk = philox4x32_10((uint32_t)c, (uint32_t)(c >> 32), 0u, 0u, (uint32_t)a.seed, (uint32_t)(a.seed >> 32));
+            }
             uint32_t packed = 0;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -58,7 +68,7 @@ quantize_rows_bf16x16(QArgs a)
                 const uint32_t word = e < 8 ? w0[e >> 1] : w1[(e - 8) >> 1];
                 const float xv = (e & 1) ? __uint_as_float(word & 0xFFFF0000u) : __uint_as_float(word << 16);
                 const float t = xv * rho;
-                const uint32_t u24 = sr.bits((uint64_t)(p0 + e) + a.offset);
+                const uint32_t u24 = aligned ? blk.v[j] >> 8 : sr.bits(g0 + e);
                 packed |= encode<FMT, MODE>(t, u24) << (8 * j);
             }
             out[q] = packed;
@@ -116,7 +126,49 @@ quantize_cols_bf16(QArgs a)
     }
     uint32_t lo[8] = {}, hi[8] = {};
     SrStream sr(a.seed);
-    if (n < N) {
+    if constexpr (MODE == QMM_ROUND_STOCHASTIC) {
+        // Column by column: the eight codes of a column are consecutive output elements, i.e. two whole Philox
+        // blocks when the column's first element number is a multiple of 4 (K and the caller's offset both are);
+        // going row by row instead would draw a fresh block for every single element.
+        if (n < N) {
+            u32x4 w[8];
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                const int64_t k = k0 + tk * 8 + kk;
+                w[kk] = u32x4{0u, 0u, 0u, 0u};
+                if (k < K) w[kk] = *reinterpret_cast<const u32x4*>(base + k * a.row_stride + n);
+            }
+            const bool aligned = ((K & 3) == 0) && ((a.offset & 3u) == 0);           // uniform over the grid
+            auto column = [&](int j, int kk, uint32_t u24) {
+                const uint32_t word = w[kk][j >> 1];
+                const float xv = (j & 1) ? __uint_as_float(word & 0xFFFF0000u) : __uint_as_float(word << 16);
+                const uint32_t code = encode<FMT, MODE>(xv * rho[j], u24);
+                if (kk < 4) lo[j] |= code << (8 * kk); else hi[j] |= code << (8 * (kk - 4));
+            };
+            const uint64_t g_first = (uint64_t)((b * N + n) * K + k0 + tk * 8) + a.offset;    // column j: + j * K
+            if (aligned) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint64_t c = (g_first + (uint64_t)j * (uint64_t)K) >> 2;
+                    const Philox4 ba = philox4x32_10((uint32_t)c, (uint32_t)(c >> 32), 0u, 0u, (uint32_t)a.seed,
+                                                     (uint32_t)(a.seed >> 32));
+                    const Philox4 bb = philox4x32_10((uint32_t)(c + 1), (uint32_t)((c + 1) >> 32), 0u, 0u, (uint32_t)a.seed,
+                                                     (uint32_t)(a.seed >> 32));
+#pragma unroll
+                    for (int kk = 0; kk < 8; ++kk) column(j, kk, (kk < 4 ? ba.v[kk] : bb.v[kk - 4]) >> 8);
+                    // one column at a time: interleaved, the sixteen generator blocks of a thread need 240 registers
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+#pragma unroll
+                    for (int kk = 0; kk < 8; ++kk) column(j, kk, sr.bits(g_first + (uint64_t)j * (uint64_t)K + kk));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+    } else if (n < N) {
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
             const int64_t k = k0 + tk * 8 + kk;

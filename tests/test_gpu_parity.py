@@ -111,18 +111,20 @@ def test_quantize_every_bf16_pattern_many_step_sizes(fmt, mode):
     deltas = torch.tensor([1.0, 0.5, 3.0, 1e-3, 7.77e-5, 123.456, 2.0 ** -126, 1.0 / 448, 1.0 / 127, 57344.0,
                            1e10, 1e-20, 0.0123, 2.0 ** -20, 17.0, 0.3333], dtype=torch.float32)
     x = pats.unsqueeze(0).repeat(16, 1).contiguous()               # [16, 65536]
-    want = O.quantize(np32(x), 1, fmt, deltas.numpy(), per_channel=True, mode=mode, seed=42, offset=7)
-    got = qmm.quantize(x.to(DEV), 1, fmt, deltas.to(DEV), per_channel=True, mode=mode, seed=42, offset=7)
-    g, w = got.cpu().numpy(), want
-    bad = np.nonzero(g != w)
-    assert bad[0].size == 0, f"first mismatch at {[b[0] for b in bad]}: got {g[bad][0]:#x} want {w[bad][0]:#x}"
+    # offset 7: random words looked up element by element; offset 8: a thread's elements are whole generator blocks
+    for offset in ((7, 8) if mode == qmm.STOCHASTIC else (0,)):
+        want = O.quantize(np32(x), 1, fmt, deltas.numpy(), per_channel=True, mode=mode, seed=42, offset=offset)
+        got = qmm.quantize(x.to(DEV), 1, fmt, deltas.to(DEV), per_channel=True, mode=mode, seed=42, offset=offset)
+        g, w = got.cpu().numpy(), want
+        bad = np.nonzero(g != w)
+        assert bad[0].size == 0, f"first mismatch at {[b[0] for b in bad]}: got {g[bad][0]:#x} want {w[bad][0]:#x}"
 
 
 @pytest.mark.parametrize("fmt", FMTS)
 @pytest.mark.parametrize("shape,contract_axis,per_channel,groups", [
     ((1, 256, 768), 1, False, 1), ((1, 768, 768), 1, True, 1), ((1, 300, 520), 0, True, 1), ((1, 300, 520), 0, False, 1),
     ((6, 64, 96), 1, True, 2), ((6, 70, 96), 0, True, 3), ((4, 33, 50), 1, False, 1), ((4, 33, 50), 0, True, 2),
-    ((2, 130, 136), 0, False, 2), ((1, 1024, 256), 0, True, 1),
+    ((2, 130, 136), 0, False, 2), ((1, 1024, 256), 0, True, 1), ((2, 264, 128), 0, True, 1), ((1, 250, 256), 0, False, 1),
 ])
 def test_quantize_paths_bit_exact(fmt, shape, contract_axis, per_channel, groups):
     x = W.student_t(shape, 4, seed=17 + shape[1])
@@ -130,11 +132,13 @@ def test_quantize_paths_bit_exact(fmt, shape, contract_axis, per_channel, groups
     d = qmm.scale(xd, contract_axis, fmt, per_channel, groups)
     want_d = O.scale(np32(x), contract_axis, fmt, per_channel, groups)
     assert np.array_equal(d.cpu().numpy(), want_d)
-    for mode in (qmm.RTNE, qmm.STOCHASTIC):
-        want = O.quantize(np32(x), contract_axis, fmt, want_d, per_channel, groups, mode, seed=5, offset=3)
-        got = qmm.quantize(xd, contract_axis, fmt, d, per_channel, groups, mode, seed=5, offset=3)
+    # stochastic rounding with offsets that do and do not keep a thread's elements on whole generator blocks (the
+    # shapes include contracting extents that are and are not multiples of 4)
+    for mode, offset in ((qmm.RTNE, 0), (qmm.STOCHASTIC, 3), (qmm.STOCHASTIC, 0), (qmm.STOCHASTIC, 1 << 33)):
+        want = O.quantize(np32(x), contract_axis, fmt, want_d, per_channel, groups, mode, seed=5, offset=offset)
+        got = qmm.quantize(xd, contract_axis, fmt, d, per_channel, groups, mode, seed=5, offset=offset)
         assert got.shape == want.shape
-        assert np.array_equal(got.cpu().numpy(), want), f"mode {mode}"
+        assert np.array_equal(got.cpu().numpy(), want), f"mode {mode} offset {offset}"
 
 
 def test_quantize_f32_input_and_gradient_like_values():
