@@ -169,21 +169,22 @@ quantize_cols_bf16(QArgs a)
             }
         }
     } else if (n < N) {
+        // rows in pairs: the FP8 formats go through the two-at-a-time hardware converter (encode_fp8_rtne_pair)
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
+        for (int kk = 0; kk < 8; kk += 2) {
             const int64_t k = k0 + tk * 8 + kk;
-            u32x4 w = {0u, 0u, 0u, 0u};
-            if (k < K) w = *reinterpret_cast<const u32x4*>(base + k * a.row_stride + n);
+            u32x4 wa = {0u, 0u, 0u, 0u}, wb = {0u, 0u, 0u, 0u};
+            if (k < K) wa = *reinterpret_cast<const u32x4*>(base + k * a.row_stride + n);
+            if (k + 1 < K) wb = *reinterpret_cast<const u32x4*>(base + (k + 1) * a.row_stride + n);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const uint32_t word = w[j >> 1];
-                const float xv = (j & 1) ? __uint_as_float(word & 0xFFFF0000u) : __uint_as_float(word << 16);
-                const float t = xv * rho[j];
-                uint32_t u24 = 0;
-                if constexpr (MODE == QMM_ROUND_STOCHASTIC)
-                    u24 = sr.bits((uint64_t)((b * N + n + j) * K + k) + a.offset);
-                const uint32_t code = encode<FMT, MODE>(t, u24);
-                if (kk < 4) lo[j] |= code << (8 * kk); else hi[j] |= code << (8 * (kk - 4));
+                const uint32_t worda = wa[j >> 1], wordb = wb[j >> 1];
+                const float ta = ((j & 1) ? __uint_as_float(worda & 0xFFFF0000u) : __uint_as_float(worda << 16)) * rho[j];
+                const float tb = ((j & 1) ? __uint_as_float(wordb & 0xFFFF0000u) : __uint_as_float(wordb << 16)) * rho[j];
+                uint32_t pair;
+                if constexpr (FMT == QMM_FMT_INT8) pair = encode_int8_rtne(ta) | (encode_int8_rtne(tb) << 8);
+                else pair = encode_fp8_rtne_pair<FMT>(ta, tb);
+                if (kk < 4) lo[j] |= pair << (8 * kk); else hi[j] |= pair << (8 * (kk - 4));
             }
         }
     }
