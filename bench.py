@@ -221,6 +221,33 @@ def main():
         return {"what": "qmm_gemm timed the same way (10 launches back to back per event pair)",
                 "tflops": round(flops / (total_ms * 1e-3) / 1e12, 1), "ms_per_launch": per_op}
     roofline["gemm_back_to_back"] = own_back_to_back()
+
+    # the same product with the noise-to-signal sums taken in its epilogue (qmm_gemm_nsr), next to the product
+    # followed by the full metric pass, both ten launches back to back per event pair
+    def fused_nsr_context():
+        def ms_of(fn):
+            ts = []
+            for it in range(4):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(10):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                if it >= 1:
+                    ts.append(e0.elapsed_time(e1) / 10)
+            return sorted(ts)[len(ts) // 2]
+        o2 = torch.empty(2, dtype=torch.float64, device=dev)
+        ws = torch.empty(4 << 20, dtype=torch.uint8, device=dev)
+        fused, separate = {}, {}
+        for st in state:
+            fused[st["op"].name] = round(ms_of(lambda: qmm.gemm_nsr((st["cx"], st["oa"]), (st["cw"], st["ob"]), st["y_ref"][0],
+                                                                    out=st["y"], out2=o2, workspace=ws)), 4)
+            separate[st["op"].name] = round(ms_of(lambda: (qmm.gemm((st["cx"], st["oa"]), (st["cw"], st["ob"]), out=st["y"]),
+                                                           qmm.metric(st["y"], st["y_ref"], out=st["m"], workspace=st["ws"]))), 4)
+        return {"what": "qmm_gemm_nsr (two sums of the noise-to-signal ratio in the epilogue) against qmm_gemm + qmm_metric "
+                        "(all 16 fields), ms per op", "gemm_nsr": fused, "gemm_then_metric": separate}
+    roofline["fused_nsr"] = fused_nsr_context()
     passes = {k: {"ms_per_step": round(per_kind_ms[k], 4),
                   "GBps": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9, 1),
                   "frac_hbm": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}

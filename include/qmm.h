@@ -171,6 +171,27 @@ qmm_status qmm_gemm(const qmm_operand* a, const qmm_operand* b,
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * qmm_gemm_nsr -- qmm_gemm with the noise-to-signal sums taken in its epilogue (the error metric the path reduces
+ * for every op, here without a second pass over Y; an extension: the paper measures, it does not say where).
+ * Computes Y exactly as qmm_gemm does and, over the values it stores (rounded to y_dtype),
+ *     out2[0] = sum (y - y_ref)^2      out2[1] = sum y_ref^2
+ * in binary64, elements whose error is NaN left out of both sums -- fields 0 and 1 of qmm_metric(Y, y_ref).  The
+ * order of additions is fixed by the shapes (per-wavefront sums folded by a second kernel), so results are
+ * reproducible run to run; it differs from qmm_metric's order, so the sums agree with it to rounding only.
+ *   a, b       8-bit operands given as codes (is_codes = 1); BF16 and quantize-on-load operands: QMM_ERR_UNSUPPORTED.
+ *   y          device [batch][M][N], required.      y_ref  device [batch][M][N] binary32, 16-byte aligned.
+ *   out2       device, 2 doubles, 8-byte aligned.
+ *   workspace  device scratch of at least qmm_gemm_nsr_workspace_size() bytes, 16-byte aligned: QMM_ERR_WORKSPACE
+ *              if missing or too small.  K is never split here.
+ * Other argument rules and errors as for qmm_gemm.  An empty output writes two zeros.
+ */
+size_t qmm_gemm_nsr_workspace_size(int64_t batch, int64_t M, int64_t N);
+qmm_status qmm_gemm_nsr(const qmm_operand* a, const qmm_operand* b,
+                        int64_t batch, int64_t M, int64_t N, int64_t K,
+                        void* y, qmm_dtype y_dtype, const float* y_ref, double* out2,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Step 6 -- error metrics of y against the high-precision result y_ref, one
  * pass, binary64 accumulation, e = y - y_ref.  out16 (device, 16 doubles):
  *   [0] sum e^2          [1] sum ref^2        (noise-to-signal ratio = [0]/[1])

@@ -76,7 +76,9 @@ def check_asm():
             findings.append(f"{nm}: {body.count('v_accvgpr_mov')} v_accvgpr_mov (accumulators copied around MFMAs)")
         tail = text[end:end + 8000]
         sc = re.search(r"; ScratchSize: (\d+)", tail)
-        if sc and int(sc.group(1)) > 0 and nm.endswith("Li0EEEvNS0_8GemmArgsE") and "shortk" not in nm:
+        targs = re.search(r"gemm_kernelI((?:Li\d+E)+)E", nm)
+        fuse = int(re.findall(r"Li(\d+)E", targs.group(1))[6]) if targs else 0      # <KIND, FA, FB, TM, TG, NWN, FUSE, NSR>
+        if sc and int(sc.group(1)) > 0 and targs and fuse == 0:                       # codes-in kernels: the throughput path
             findings.append(f"{nm}: {sc.group(1)} bytes of scratch per lane")
         if sc and int(sc.group(1)) > 0 and "shortk" in nm:
             findings.append(f"{nm}: {sc.group(1)} bytes of scratch per lane")

@@ -72,6 +72,9 @@ struct GemmArgs {
     int direct_along_n;               // gemm_direct_kernel: the workgroup's four wavefronts lie along n (else along m)
     int splits;                       // split-K: workgroups per output tile (1 = none); partial sums go to `partial`
     void* partial;                    // [splits][batch][M][N] raw accumulators (int32 / float)
+    const float* nsr_ref;             // NSR variant: high-precision product [batch][M][N], else null
+    double* nsr_partial;              // NSR variant: per wavefront {sum (y - ref)^2, sum ref^2}
+    double* nsr_out;                  // NSR variant: the two folded sums
 };
 
 // 16 bytes per lane from global memory into LDS: lane l lands at lds_unit + 16*l.
@@ -123,7 +126,10 @@ template <typename AccT, int NI, int NJ> QMM_DEV void pin_accumulators(AccT (&ac
 // FUSE: bit 0 / bit 1 = the A / B operand arrives as bfloat16 values and is quantized (RTNE, with its step sizes)
 // while it is staged into LDS; otherwise it arrives as 8-bit codes and is copied by LDS-DMA.
 // NWN: wavefronts along N (2 or 4): the workgroup has 2 x NWN wavefronts, NWN / 2 on every SIMD.
-template <int KIND, int FA, int FB, int TM, int TG, int NWN, int FUSE>
+// NSR: the epilogue also reads the high-precision product and accumulates, per wavefront and in binary64, the two
+// sums of the noise-to-signal ratio over the values it stores (y as rounded to the output type): sum (y - ref)^2
+// and sum ref^2, elements whose error is NaN left out as in qmm_metric.  No second pass over Y.
+template <int KIND, int FA, int FB, int TM, int TG, int NWN, int FUSE, int NSR = 0>
 __global__ void __launch_bounds__(64 * kWavesM * NWN, 1)
 gemm_kernel(GemmArgs g)
 {
@@ -567,6 +573,21 @@ gemm_kernel(GemmArgs g)
     };
     auto row_in_block = [&](int r) -> int { return F8 ? lane_row + r : 8 * (r >> 2) + lane_row + (r & 3); };
 
+    double nsr_ee = 0.0, nsr_rr = 0.0;
+    auto nsr_add = [&](float stored, float ref) {
+        const double e = (double)stored - (double)ref;
+        if (e == e) { nsr_ee = fma(e, e, nsr_ee); nsr_rr = fma((double)ref, (double)ref, nsr_rr); }
+    };
+    // TILES_N consecutive reference values of output row (matrix bidx, row m), from column n on (whole tiles only)
+    auto nsr_row = [&](int64_t m, float (&rv)[TILES_N]) {
+        const float* p = g.nsr_ref + (bidx * g.M + m) * g.N + n;
+        if constexpr (TILES_N == 4) { const v4f q = *reinterpret_cast<const v4f*>(p); rv[0] = q[0]; rv[1] = q[1]; rv[2] = q[2]; rv[3] = q[3]; }
+        else if constexpr (TILES_N == 2) { typedef float f2v __attribute__((ext_vector_type(2))); const f2v q = *reinterpret_cast<const f2v*>(p); rv[0] = q[0]; rv[1] = q[1]; }
+        else {
+#pragma unroll
+            for (int tt = 0; tt < TILES_N; ++tt) rv[tt] = p[tt];
+        }
+    };
     const bool interior = (m0 + BM <= g.M) && (n0 + BN <= g.N) && (g.N % TILES_N == 0);
     if (g.splits > 1) {
         // split-K: the raw accumulators of this K range go to the partial-sum buffer; a second kernel adds the
@@ -631,7 +652,16 @@ gemm_kernel(GemmArgs g)
             for (int r = 0; r < REGS; ++r) {
                 const int ml = ia * R + row_in_block(r);
                 uint32_t pk[TILES_N / 2];
+                float rv[TILES_N];
+                if constexpr (NSR != 0) nsr_row(m_base + ml, rv);
                 packed_row(ia, r, pk);
+                if constexpr (NSR != 0) {
+#pragma unroll
+                    for (int q = 0; q < TILES_N / 2; ++q) {
+                        nsr_add(__uint_as_float(pk[q] << 16), rv[2 * q]);
+                        nsr_add(__uint_as_float(pk[q] & 0xFFFF0000u), rv[2 * q + 1]);
+                    }
+                }
                 uint8_t* dst = ybase + ml * row_bytes;
                 if constexpr (TILES_N == 8) *reinterpret_cast<u32x4*>(dst) = u32x4{pk[0], pk[1], pk[2], pk[3]};
                 else if constexpr (TILES_N == 4) *reinterpret_cast<u32x2*>(dst) = u32x2{pk[0], pk[1]};
@@ -661,12 +691,18 @@ gemm_kernel(GemmArgs g)
             for (int r = 0; r < REGS; ++r) {
                 const int ml = ia * R + row_in_block(r);
                 float* dst = ybase + (int64_t)ml * g.N;
+                float rv[TILES_N];
+                if constexpr (NSR != 0) nsr_row(m_base + ml, rv);
 #pragma unroll
                 for (int q = 0; q < TILES_N / 4; ++q) {
                     uint32_t raw;
                     v4f v;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = value(ia, r, 4 * q + e, sl_rows[ia][r], raw);
+                    if constexpr (NSR != 0) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) nsr_add(v[e], rv[4 * q + e]);
+                    }
                     *reinterpret_cast<v4f*>(dst + 4 * q) = v;
                 }
             }
@@ -693,12 +729,38 @@ gemm_kernel(GemmArgs g)
                                 if (g.y_bf16) static_cast<__bf16*>(g.y)[o + tt] = (__bf16)v;
                                 else static_cast<float*>(g.y)[o + tt] = v;
                             }
+                            if constexpr (NSR != 0) nsr_add(g.y_bf16 ? (float)(__bf16)v : v, g.nsr_ref[o + tt]);
                         }
                     }
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+    }
+    if constexpr (NSR != 0) {
+        // one pair of sums per wavefront; a second kernel folds them in a fixed order
+        const double see = wave_sum_f64(nsr_ee), srr = wave_sum_f64(nsr_rr);
+        if (lane == 0) {
+            double* o = g.nsr_partial + ((int64_t)blockIdx.x * NWAVES + wave) * 2;
+            o[0] = see; o[1] = srr;
+        }
+    }
+}
+
+// Fold of the NSR variant's per-wavefront sums: thread t takes pairs t, t + 256, ... in ascending order, then the
+// fixed shuffle tree and the four wavefronts in order: the order of additions depends on the count only.
+__global__ void __launch_bounds__(256)
+nsr_finalize(const double* __restrict__ partial, int64_t count, double* __restrict__ out2)
+{
+    __shared__ double s[4][2];
+    double ee = 0.0, rr = 0.0;
+    for (int64_t i = threadIdx.x; i < count; i += 256) { ee += partial[2 * i]; rr += partial[2 * i + 1]; }
+    ee = wave_sum_f64(ee); rr = wave_sum_f64(rr);
+    if ((threadIdx.x & 63) == 0) { s[threadIdx.x >> 6][0] = ee; s[threadIdx.x >> 6][1] = rr; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        out2[0] = ((s[0][0] + s[1][0]) + s[2][0]) + s[3][0];
+        out2[1] = ((s[0][1] + s[1][1]) + s[2][1]) + s[3][1];
     }
 }
 
@@ -1246,7 +1308,7 @@ int plan_splits(int64_t M, int64_t N, int64_t rowbytes, int64_t batch, int fuse)
     return splits >= 2 ? (int)splits : 1;
 }
 
-template <int KIND, int FA, int FB, int TM, int TG, int NWN, int FUSE>
+template <int KIND, int FA, int FB, int TM, int TG, int NWN, int FUSE, int NSR = 0>
 qmm_status launch_tile(GemmArgs& g, hipStream_t s)
 {
     constexpr int BM = kWavesM * 32 * TM, BN = NWN * 64 * TG;
@@ -1255,7 +1317,7 @@ qmm_status launch_tile(GemmArgs& g, hipStream_t s)
     g.tiles_n = (int)((g.N + BN - 1) / BN);
     const int64_t total = (int64_t)g.tiles_m * g.tiles_n * g.batch * g.splits;
     if (total > 0x7FFFFFFF) return QMM_ERR_UNSUPPORTED;
-    auto kern = gemm_kernel<KIND, FA, FB, TM, TG, NWN, FUSE>;
+    auto kern = gemm_kernel<KIND, FA, FB, TM, TG, NWN, FUSE, NSR>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
@@ -1263,6 +1325,10 @@ qmm_status launch_tile(GemmArgs& g, hipStream_t s)
         attr_set = true;
     }
     kern<<<(unsigned)total, 64 * kWavesM * NWN, LDS_BYTES, s>>>(g);
+    if constexpr (NSR != 0) {
+        if (hipGetLastError() != hipSuccess) return QMM_ERR_LAUNCH;
+        nsr_finalize<<<1, 256, 0, s>>>(g.nsr_partial, total * kWavesM * NWN, g.nsr_out);
+    }
     if (g.splits > 1) {
         if (hipGetLastError() != hipSuccess) return QMM_ERR_LAUNCH;
         const int64_t threads = g.batch * g.M * ((g.N + 3) / 4);
@@ -1326,6 +1392,14 @@ qmm_status launch_shortk(GemmArgs& g, hipStream_t s)
 template <int KIND, int FA, int FB, int FUSE>
 qmm_status launch_fuse(GemmArgs& g, hipStream_t s)
 {
+    if constexpr (FUSE == 0 && KIND != KIND_BF16) {
+        if (g.nsr_ref) {      // the variant that also accumulates the noise-to-signal sums: gemm_kernel only, no split
+            const int64_t big_tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
+            if (big_tiles >= 192 && g.M > 128 && g.N > 128) return launch_tile<KIND, FA, FB, 4, 1, 4, 0, 1>(g, s);
+            return launch_tile<KIND, FA, FB, 2, 1, 2, 0, 1>(g, s);
+        }
+    }
+    if (g.nsr_ref) return QMM_ERR_UNSUPPORTED;
     if constexpr (FUSE == 0) {
         if (use_direct(g, 0)) return launch_direct<KIND, FA, FB>(g, s);
         if (use_shortk<KIND>(g, 0)) return launch_shortk<KIND, FA, FB>(g, s);
@@ -1382,10 +1456,20 @@ extern "C" size_t qmm_gemm_workspace_size(const qmm_operand* a, const qmm_operan
     return splits > 1 ? (size_t)splits * (size_t)batch * (size_t)M * (size_t)N * 4u : 0;
 }
 
-extern "C" qmm_status qmm_gemm(const qmm_operand* a, const qmm_operand* b, int64_t batch, int64_t M, int64_t N, int64_t K,
-                               void* y, qmm_dtype y_dtype, void* acc_out, void* workspace, size_t workspace_bytes,
-                               void* stream)
+namespace {
+size_t nsr_workspace_bytes(int64_t batch, int64_t M, int64_t N)
 {
+    // a pair of binary64 sums per wavefront; 128 x 128 tiles of four wavefronts are the finest partition used
+    const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128) * batch;
+    return (size_t)(tiles > 0 ? tiles : 1) * 4u * 2u * sizeof(double);
+}
+
+// qmm_gemm, and with y_ref != NULL the variant that also accumulates the noise-to-signal sums into nsr_out2.
+qmm_status gemm_impl(const qmm_operand* a, const qmm_operand* b, int64_t batch, int64_t M, int64_t N, int64_t K,
+                     void* y, qmm_dtype y_dtype, void* acc_out, const float* y_ref, double* nsr_out2,
+                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    const bool nsr = y_ref != nullptr;
     qmm_status st = check_operand(a);
     if (st != QMM_OK) return st;
     st = check_operand(b);
@@ -1397,6 +1481,14 @@ extern "C" qmm_status qmm_gemm(const qmm_operand* a, const qmm_operand* b, int64
     if (!bf && ((a->format == QMM_FMT_INT8) != (b->format == QMM_FMT_INT8))) return QMM_ERR_UNSUPPORTED;
     const int fuse = bf ? 0 : ((a->is_codes ? 0 : 1) | (b->is_codes ? 0 : 2));
     if (!y && !acc_out) return QMM_ERR_NULL;
+    if (nsr) {
+        if (bf || fuse != 0) return QMM_ERR_UNSUPPORTED;
+        if (!y || !nsr_out2) return QMM_ERR_NULL;
+        if (acc_out) return QMM_ERR_UNSUPPORTED;
+        if (!aligned16(y_ref) || (reinterpret_cast<uintptr_t>(nsr_out2) & 7u)) return QMM_ERR_ALIGN;
+        if (!workspace || workspace_bytes < nsr_workspace_bytes(batch, M, N)) return QMM_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return QMM_ERR_ALIGN;
+    }
     if (batch * M * N == 0) return QMM_OK;
     if (!bf && (!a->delta || !b->delta)) return QMM_ERR_NULL;
     const int64_t esz = bf ? 2 : 1;
@@ -1415,7 +1507,8 @@ extern "C" qmm_status qmm_gemm(const qmm_operand* a, const qmm_operand* b, int64
     g.db_inner = b->gran.batch_inner > 0 ? b->gran.batch_inner : 1;
     g.da_per_channel = a->gran.per_channel; g.db_per_channel = b->gran.per_channel;
     g.y = y; g.y_bf16 = y_dtype == QMM_DT_BF16; g.acc_out = acc_out;
-    g.splits = plan_splits(M, N, g.rowbytes, batch, fuse);
+    g.splits = nsr ? 1 : plan_splits(M, N, g.rowbytes, batch, fuse);
+    if (nsr) { g.nsr_ref = y_ref; g.nsr_partial = static_cast<double*>(workspace); g.nsr_out = nsr_out2; }
     if (g.splits > 1) {
         const size_t need = (size_t)g.splits * (size_t)batch * (size_t)M * (size_t)N * 4u;
         if (!workspace || workspace_bytes < need) return QMM_ERR_WORKSPACE;
@@ -1430,4 +1523,37 @@ extern "C" qmm_status qmm_gemm(const qmm_operand* a, const qmm_operand* b, int64
     if (a->format == QMM_FMT_E4M3) return launch_kind<KIND_F8, QMM_FMT_E4M3, QMM_FMT_E5M2>(g, s, fuse);
     if (b->format == QMM_FMT_E4M3) return launch_kind<KIND_F8, QMM_FMT_E5M2, QMM_FMT_E4M3>(g, s, fuse);
     return launch_kind<KIND_F8, QMM_FMT_E5M2, QMM_FMT_E5M2>(g, s, fuse);
+}
+}  // namespace
+
+extern "C" qmm_status qmm_gemm(const qmm_operand* a, const qmm_operand* b, int64_t batch, int64_t M, int64_t N, int64_t K,
+                               void* y, qmm_dtype y_dtype, void* acc_out, void* workspace, size_t workspace_bytes,
+                               void* stream)
+{
+    return gemm_impl(a, b, batch, M, N, K, y, y_dtype, acc_out, nullptr, nullptr, workspace, workspace_bytes, stream);
+}
+
+extern "C" size_t qmm_gemm_nsr_workspace_size(int64_t batch, int64_t M, int64_t N)
+{
+    if (batch < 0 || M < 0 || N < 0) return 0;
+    return nsr_workspace_bytes(batch, M, N);
+}
+
+extern "C" qmm_status qmm_gemm_nsr(const qmm_operand* a, const qmm_operand* b, int64_t batch, int64_t M, int64_t N,
+                                   int64_t K, void* y, qmm_dtype y_dtype, const float* y_ref, double* out2,
+                                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (batch >= 0 && M >= 0 && N >= 0 && K >= 0 && batch * M * N == 0) {
+        // an empty output (its pointers may be NULL): both sums are zero
+        qmm_status st = check_operand(a);
+        if (st != QMM_OK) return st;
+        st = check_operand(b);
+        if (st != QMM_OK) return st;
+        if (!out2) return QMM_ERR_NULL;
+        if (reinterpret_cast<uintptr_t>(out2) & 7u) return QMM_ERR_ALIGN;
+        nsr_finalize<<<1, 256, 0, as_stream(stream)>>>(nullptr, 0, out2);
+        return launch_status();
+    }
+    if (!y_ref) return QMM_ERR_NULL;
+    return gemm_impl(a, b, batch, M, N, K, y, y_dtype, nullptr, y_ref, out2, workspace, workspace_bytes, stream);
 }

@@ -14,7 +14,7 @@ DT_BF16, DT_F32 = 0, 1
 RTNE, STOCHASTIC = 0, 1
 FORMATS = {"int8": INT8, "e4m3": E4M3, "e5m2": E5M2, "bf16": BF16}
 EXPORTS = ["qmm_num_scales", "qmm_scale_workspace_size", "qmm_scale", "qmm_quantize", "qmm_gemm_workspace_size",
-           "qmm_gemm", "qmm_metric_workspace_size", "qmm_metric", "qmm_dequantize", "qmm_moments_workspace_size", "qmm_moments", "qmm_mfma_rate", "qmm_status_string", "qmm_version"]
+           "qmm_gemm", "qmm_gemm_nsr_workspace_size", "qmm_gemm_nsr", "qmm_metric_workspace_size", "qmm_metric", "qmm_dequantize", "qmm_moments_workspace_size", "qmm_moments", "qmm_mfma_rate", "qmm_status_string", "qmm_version"]
 
 
 class QmmError(RuntimeError):
@@ -57,6 +57,8 @@ def lib():
         L.qmm_quantize.restype = i32; L.qmm_quantize.argtypes = [TP, i32, GP, vp, i32, u64, u64, vp, vp]
         L.qmm_gemm_workspace_size.restype = sz; L.qmm_gemm_workspace_size.argtypes = [OP, OP, i64, i64, i64, i64]
         L.qmm_gemm.restype = i32; L.qmm_gemm.argtypes = [OP, OP, i64, i64, i64, i64, vp, i32, vp, vp, sz, vp]
+        L.qmm_gemm_nsr_workspace_size.restype = sz; L.qmm_gemm_nsr_workspace_size.argtypes = [i64, i64, i64]
+        L.qmm_gemm_nsr.restype = i32; L.qmm_gemm_nsr.argtypes = [OP, OP, i64, i64, i64, i64, vp, i32, vp, vp, vp, sz, vp]
         L.qmm_metric_workspace_size.restype = sz; L.qmm_metric_workspace_size.argtypes = [i64]
         L.qmm_metric.restype = i32; L.qmm_metric.argtypes = [vp, i32, vp, vp, i64, vp, vp, sz, vp]
         L.qmm_dequantize.restype = i32; L.qmm_dequantize.argtypes = [vp, i64, i64, i64, i32, GP, vp, vp, i32, vp]
@@ -170,6 +172,27 @@ def gemm(a, b, out_dtype=torch.float32, want_acc=False, out=None, acc_out=None, 
     _check(L.qmm_gemm(ctypes.byref(oa), ctypes.byref(ob), bt, m, n, k, y.data_ptr() if y is not None else None, ydt,
                       acc.data_ptr() if acc is not None else None, ws.data_ptr(), ws.numel(), _stream()), "qmm_gemm")
     return (y, acc) if want_acc else y
+
+
+def gemm_nsr(a, b, y_ref, out_dtype=torch.bfloat16, out=None, out2=None, workspace=None):
+    """qmm_gemm_nsr: y as `gemm` gives it, and a device tensor of 2 float64: sum (y - y_ref)^2, sum y_ref^2."""
+    L = lib()
+    (ta, oa), (tb, ob) = a, b
+    if ta.dim() == 2:
+        ta = ta.unsqueeze(0); tb = tb.unsqueeze(0)
+    bt, m, k = ta.shape
+    n = tb.shape[1]
+    assert tb.shape[0] == bt and tb.shape[2] == k
+    assert y_ref.dtype == torch.float32 and y_ref.is_contiguous() and y_ref.numel() == bt * m * n
+    dev = ta.device
+    y = out if out is not None else torch.empty((bt, m, n), dtype=out_dtype, device=dev)
+    if out2 is None:
+        out2 = torch.empty(2, dtype=torch.float64, device=dev)
+    ws = workspace if workspace is not None else _workspace(L.qmm_gemm_nsr_workspace_size(bt, m, n), dev)
+    ydt = DT_BF16 if y.dtype == torch.bfloat16 else DT_F32
+    _check(L.qmm_gemm_nsr(ctypes.byref(oa), ctypes.byref(ob), bt, m, n, k, y.data_ptr(), ydt, y_ref.data_ptr(),
+                          out2.data_ptr(), ws.data_ptr(), ws.numel(), _stream()), "qmm_gemm_nsr")
+    return y, out2
 
 
 def quantized_operand(x, contract_axis, fmt, per_channel=False, batch_groups=1, mode=RTNE, seed=0, batch_inner=1):

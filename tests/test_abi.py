@@ -95,3 +95,23 @@ def test_argument_errors_are_reported_before_any_launch(L):
     assert L.qmm_dequantize(None, 1, 4, 16, qmm.E4M3, ctypes.byref(g), fake, fake, 1, None) == 1
     assert L.qmm_dequantize(fake, 1, 4, 16, qmm.E4M3, ctypes.byref(g), fake, ctypes.c_void_p(0x1002), 1, None) == 4
     assert L.qmm_dequantize(None, 0, 4, 16, qmm.E4M3, ctypes.byref(g), None, fake, 1, None) == 0
+
+
+def test_gemm_nsr_argument_errors(L):
+    fake = ctypes.c_void_p(0x1000)
+    ga = qmm.granularity(False, 1)
+    codes = qmm.Operand(fake, qmm.E4M3, 1, fake, ga)
+    raw = qmm.Operand(fake, qmm.E4M3, 0, fake, ga)               # quantize-on-load operand
+    bf = qmm.Operand(fake, qmm.BF16, 0, None, ga)
+    need = L.qmm_gemm_nsr_workspace_size(1, 256, 256)
+    assert need >= 4 * 4 * 16 and L.qmm_gemm_nsr_workspace_size(-1, 1, 1) == 0
+    args = (1, 256, 256, 128)
+    call = lambda a, b, y, ref, out2, ws, nws: L.qmm_gemm_nsr(ctypes.byref(a), ctypes.byref(b), *args, y, qmm.DT_BF16, ref, out2, ws, nws, None)
+    assert call(codes, codes, fake, None, fake, fake, need) == 1            # no reference
+    assert call(codes, codes, None, fake, fake, fake, need) == 1            # no output
+    assert call(codes, codes, fake, fake, None, fake, need) == 1            # no place for the sums
+    assert call(raw, codes, fake, fake, fake, fake, need) == 5              # quantize-on-load operand
+    assert call(bf, bf, fake, fake, fake, fake, need) == 5                  # reference product
+    assert call(codes, codes, fake, fake, fake, None, 0) == 6               # no workspace
+    assert call(codes, codes, fake, fake, fake, fake, need - 1) == 6        # workspace too small
+    assert call(codes, codes, fake, ctypes.c_void_p(0x1004), fake, fake, need) == 4   # misaligned reference

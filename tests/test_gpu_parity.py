@@ -350,6 +350,49 @@ def test_gemm_quantize_on_load_matches_separate_quantize(shape, fa, fb, per_chan
     assert torch.equal(yb0.view(torch.int16), yb1.view(torch.int16))
 
 
+@pytest.mark.parametrize("fmt", [qmm.INT8, qmm.E4M3])
+@pytest.mark.parametrize("shape", [(1, 512, 512, 256), (1, 300, 264, 144), (3, 130, 80, 64), (1, 1024, 1792, 128), (2, 257, 512, 272)])
+@pytest.mark.parametrize("out_dtype", [torch.bfloat16, torch.float32])
+def test_gemm_with_noise_to_signal_sums_in_the_epilogue(shape, fmt, out_dtype):
+    """qmm_gemm_nsr: Y identical to qmm_gemm's, and its two sums equal to fields 0 and 1 of the metric of that Y
+    (device pass and oracle), whole and ragged tiles, both tile sizes, both scale granularities."""
+    bt, M, N, K = shape
+    x = W.student_t((bt, M, K), 4, seed=M + K); w = W.normal((bt, N, K), 0.02, seed=N + K)
+    xd, wd = x.to(DEV), w.to(DEV)
+    ref = qmm.reference_gemm(xd, wd)
+    for pc in (False, True):
+        (cx, ox), dx = qmm.quantized_operand(xd, 1, fmt, pc)
+        (cw, ow), dw = qmm.quantized_operand(wd, 1, fmt, pc)
+        y0 = qmm.gemm((cx, ox), (cw, ow), out_dtype)
+        y1, sums = qmm.gemm_nsr((cx, ox), (cw, ow), ref, out_dtype)
+        assert torch.equal(y0.view(torch.int16 if out_dtype == torch.bfloat16 else torch.int32),
+                           y1.view(torch.int16 if out_dtype == torch.bfloat16 else torch.int32))
+        got = sums.cpu().numpy()
+        dev_metric = qmm.metric(y0, ref).cpu().numpy()
+        want = O.metric(np32(y0), ref.cpu().numpy())
+        for i in (0, 1):
+            assert abs(got[i] - dev_metric[i]) <= 1e-10 * dev_metric[i]
+            assert abs(got[i] - want[i]) <= 1e-10 * want[i]
+    # an element whose error is NaN is left out of both sums, as in the metric
+    ref2 = ref.clone(); ref2.view(-1)[5] = float("nan"); ref2.view(-1)[ref2.numel() - 3] = float("inf")
+    _, sums = qmm.gemm_nsr((cx, ox), (cw, ow), ref2, out_dtype)
+    want = O.metric(np32(y0), ref2.cpu().numpy())
+    got = sums.cpu().numpy()
+    assert np.isfinite(want[0]) == np.isfinite(got[0])
+    if np.isfinite(want[0]):
+        assert abs(got[0] - want[0]) <= 1e-10 * want[0]
+    assert got[1] == want[1] or abs(got[1] - want[1]) <= 1e-10 * abs(want[1])
+
+
+def test_gemm_nsr_empty_output_gives_zero_sums():
+    a = torch.zeros((1, 0, 64), dtype=torch.uint8, device=DEV); b = torch.zeros((1, 32, 64), dtype=torch.uint8, device=DEV)
+    d = torch.ones(1, device=DEV)
+    ref = torch.zeros((1, 0, 32), dtype=torch.float32, device=DEV)
+    out2 = torch.full((2,), 7.0, dtype=torch.float64, device=DEV)
+    qmm.gemm_nsr((a, qmm.operand(a, qmm.E4M3, d)), (b, qmm.operand(b, qmm.E4M3, d)), ref, out2=out2)
+    assert out2.cpu().tolist() == [0.0, 0.0]
+
+
 def test_reference_gemm():
     for (bt, M, N, K) in [(1, 256, 768, 768), (2, 100, 72, 200), (1, 130, 258, 520), (1, 200, 264, 4104),   # last: split-K
                           (36, 250, 250, 56), (66, 500, 40, 72),                      # fragments straight to registers
