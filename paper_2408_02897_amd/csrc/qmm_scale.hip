@@ -102,6 +102,29 @@ absmax_rows(const T* __restrict__ x, int64_t batch_stride, int64_t row_stride, i
     if (lane == 0) partial[wr] = m;
 }
 
+// Short rows (at most 256 bfloat16 columns, 16-byte aligned rows): LPR lanes per row, one 16-byte vector each, so a
+// wavefront takes 64 / LPR rows at once instead of one (with the rows dense in memory it reads 1 KB contiguous).
+template <int LPR> __global__ void __launch_bounds__(kThreads)
+absmax_rows_short(const uint16_t* __restrict__ x, int64_t batch_stride, int64_t row_stride, int64_t rows, int64_t cols,
+                  int64_t total_rows, uint32_t* __restrict__ partial)
+{
+    constexpr int RPW = kWave / LPR;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t w = (int64_t)blockIdx.x * (kThreads / kWave) + threadIdx.x / kWave;
+    const int64_t row = w * RPW + lane / LPR;
+    const int v = lane % LPR;
+    uint32_t m = 0;
+    if (row < total_rows && v < cols / 8) {
+        const int64_t b = row / rows, r = row - b * rows;
+        u16x2 mm[4] = {};
+        fold_bf16x8(*reinterpret_cast<const u32x4*>(x + b * batch_stride + r * row_stride + v * 8), mm);
+        m = finish_bf16(mm);
+    }
+#pragma unroll
+    for (int off = LPR / 2; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off, kWave));
+    if (v == 0 && row < total_rows) partial[row] = m;
+}
+
 // Column groups: workgroup = 32 column-vectors (256 columns) x 8 row lanes over a slab of rows.
 // partial[(b*nslab + slab)*cols + c].  bfloat16, cols % 8 == 0, 16-byte aligned rows.
 __global__ void __launch_bounds__(kThreads)
@@ -177,9 +200,14 @@ finalize_single(const uint32_t* __restrict__ partial, int64_t batch, int64_t P, 
         }
         m = max(max(v[0], v[1]), max(v[2], v[3]));
     } else {
-        for (int64_t q = g; q * inner < batch; q += G)
-            for (int64_t b = q * inner; b < min(batch, (q + 1) * inner); ++b)
-                for (int64_t p = threadIdx.x; p < P; p += kThreads) m = max(m, partial[b * P + p]);
+        // the (matrix, partial) pairs of the group, spread over the threads: the k-th matrix of group g is
+        // b = ((k / inner) * G + g) * inner + k % inner, increasing with k
+        for (int64_t it = threadIdx.x;; it += kThreads) {
+            const int64_t k = it / P, p = it - k * P;
+            const int64_t b = ((k / inner) * G + g) * inner + k % inner;
+            if (b >= batch) break;
+            m = max(m, partial[b * P + p]);
+        }
     }
     m = block_max_u32(m);
     if (threadIdx.x == 0) delta[g] = delta_from_absmax_bits(m, qmax);
@@ -195,16 +223,22 @@ finalize_channels(const uint32_t* __restrict__ partial, int64_t batch, int64_t P
     const int64_t g = blockIdx.y;
     uint32_t m = 0;
     if (c < C) {
-        for (int64_t q = g; q * inner < batch; q += G)
-        for (int64_t b = q * inner; b < min(batch, (q + 1) * inner); ++b) {
-            const uint32_t* base = partial + b * P * C + c;
-            int64_t p = pl;
-            for (; p + 24 < P; p += 32) {      // four loads in flight
-                const uint32_t v0 = base[p * C], v1 = base[(p + 8) * C], v2 = base[(p + 16) * C], v3 = base[(p + 24) * C];
-                m = max(m, max(max(v0, v1), max(v2, v3)));
-            }
-            for (; p < P; p += 8) m = max(m, base[p * C]);
+        // the (matrix, partial) pairs of the group over the eight lanes of a channel (k-th matrix of group g:
+        // b = ((k / inner) * G + g) * inner + k % inner, increasing with k), four loads in flight
+        auto item = [&](int64_t it) -> uint32_t {
+            const int64_t k = it / P, p = it - k * P;
+            const int64_t b = ((k / inner) * G + g) * inner + k % inner;
+            return b < batch ? partial[(b * P + p) * C + c] : 0u;
+        };
+        const int64_t groups_of_inner = (batch + inner - 1) / inner;                     // q = 0 .. groups_of_inner - 1
+        const int64_t nq = groups_of_inner > g ? (groups_of_inner - g + G - 1) / G : 0;  // those with q % G == g
+        const int64_t nitems = nq * inner * P;                                           // (items past the batch read as 0)
+        int64_t it = pl;
+        for (; it + 24 < nitems; it += 32) {
+            const uint32_t v0 = item(it), v1 = item(it + 8), v2 = item(it + 16), v3 = item(it + 24);
+            m = max(m, max(max(v0, v1), max(v2, v3)));
         }
+        for (; it < nitems; it += 8) m = max(m, item(it));
     }
     s[pl][cl] = m;
     __syncthreads();
@@ -220,6 +254,7 @@ struct Plan {
     int64_t P;        // partials per matrix (per channel for the column kinds)
     int64_t C;        // channels
     int flat_blocks;
+    bool vec;         // bfloat16 with 16-byte aligned rows of whole 8-element vectors
 };
 
 bool valid_tensor(const qmm_tensor* x, qmm_status* st)
@@ -241,6 +276,7 @@ Plan make_plan(const qmm_tensor* x, const qmm_granularity* g)
     const bool bf16 = x->dtype == QMM_DT_BF16;
     const bool vec_ok = bf16 && aligned16(x->data) && (x->cols % 8 == 0) && (x->row_stride % 8 == 0) &&
                         (x->batch_stride % 8 == 0);
+    p.vec = vec_ok;
     if (!g->per_channel) {
         p.C = 1;
         const int64_t n = x->rows * x->cols;
@@ -322,7 +358,17 @@ extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_g
         case Plan::ROWS: {
             const int64_t total = x->batch * x->rows;
             const unsigned nb = (unsigned)((total + kThreads / kWave - 1) / (kThreads / kWave));
-            if (bf16)
+            if (p.vec && x->cols <= 256) {
+                const uint16_t* xp = static_cast<const uint16_t*>(x->data);
+                const int nvec = (int)(x->cols / 8);
+                const int lpr = nvec <= 1 ? 1 : nvec <= 2 ? 2 : nvec <= 4 ? 4 : nvec <= 8 ? 8 : nvec <= 16 ? 16 : 32;
+                const int64_t waves = (total + kWave / lpr - 1) / (kWave / lpr);
+                const unsigned nbs = (unsigned)((waves + kThreads / kWave - 1) / (kThreads / kWave));
+#define QMM_ROWS_SHORT(L) absmax_rows_short<L><<<nbs, kThreads, 0, s>>>(xp, x->batch_stride, x->row_stride, x->rows, x->cols, total, partial)
+                if (lpr == 1) QMM_ROWS_SHORT(1); else if (lpr == 2) QMM_ROWS_SHORT(2); else if (lpr == 4) QMM_ROWS_SHORT(4);
+                else if (lpr == 8) QMM_ROWS_SHORT(8); else if (lpr == 16) QMM_ROWS_SHORT(16); else QMM_ROWS_SHORT(32);
+#undef QMM_ROWS_SHORT
+            } else if (bf16)
                 absmax_rows<uint16_t><<<nb, kThreads, 0, s>>>(static_cast<const uint16_t*>(x->data), x->batch_stride,
                                                                x->row_stride, x->rows, x->cols, total, partial);
             else

@@ -66,7 +66,9 @@ def all_bf16_patterns():
     ((1, 256, 768), 1, False, 1), ((1, 768, 768), 1, True, 1), ((1, 300, 520), 0, True, 1),
     ((1, 777, 1024), 1, False, 1), ((6, 64, 96), 1, False, 3), ((6, 64, 96), 1, True, 2),
     ((6, 70, 96), 0, True, 3), ((4, 33, 50), 1, False, 1), ((4, 33, 50), 0, True, 2), ((4, 33, 50), 1, True, 4),
-    ((1, 4096, 2048), 1, False, 1), ((1, 1, 8), 1, False, 1), ((2, 1000, 72), 0, False, 2),
+    ((1, 4096, 2048), 1, False, 1), ((1, 1, 8), 1, False, 1), ((2, 1000, 72), 0, False, 2),    # short rows (several rows per wavefront) and many small matrices folded per group
+    ((40, 37, 64), 1, True, 8), ((5, 19, 24), 1, True, 1), ((3, 50, 8), 1, True, 3), ((7, 11, 256), 1, True, 7),
+    ((3, 9, 136), 1, True, 1), ((96, 16, 64), 1, False, 12), ((96, 16, 64), 0, True, 12), ((600, 8, 16), 1, False, 2),
 ])
 @pytest.mark.parametrize("fmt", FMTS)
 def test_scale_bit_exact(shape, contract_axis, per_channel, groups, fmt):
