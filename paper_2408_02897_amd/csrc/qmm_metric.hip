@@ -5,31 +5,51 @@
 // private sums, wavefronts fold them by shuffles, workgroups through LDS, and a
 // small second kernel (one workgroup per field) folds the per-workgroup partials in a fixed order:
 // no atomics, so the result is reproducible run to run.
+#include <algorithm>
 #include "qmm_device.h"
 
 namespace qmm {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxBlocks = 2048;   // 8 workgroups per CU; also 8 partials per thread in the final fold
+constexpr int kMaxBlocks = 1024;   // 4 workgroups per CU (what 126 registers keep resident); also 4 partials per thread in the final fold
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-// n / d for finite n >= 0 and finite d > 0 that were converted from binary32 (exponents within +-150 or so, differences
-// of two such values included).  This is the usual reciprocal-refinement division -- hardware reciprocal estimate,
-// two Newton steps on it, the quotient, one residual correction -- i.e. what the compiler emits for `/` on binary64
-// without the operand pre-scaling and the special-case fix-up around it, neither of which can trigger in this
-// exponent range: the bits are those of the IEEE quotient, for 8 instructions instead of 11.  (The metric pass is
-// as much ALU- as HBM-bound; this division is its largest single cost.)
-QMM_DEV double quotient_plain(double n, double d)
+// Quotients n / d in binary64 for finite n >= 0 and finite d > 0 where d was converted from binary32 (24 significant
+// bits) and n is such a value or the difference of two (exponents within +-150 or so).
+//
+// reciprocals4: the four reciprocals from ONE hardware estimate: p = d0 d1 d2 d3 (within 2^-596 .. 2^512), two Newton
+// steps on rcp(p), then multiplied back by the other factors.  Each x[i] is 1 / d[i] to a few 2^-53.
+// quotient_with: q0 = n x, r = n - d q0 (exact in one fused multiply-add: d q0 has 77 bits of which all but 25 cancel),
+// q = fl(q0 + r x).  q0 + r x differs from n / d by |r / d| * |x d - 1| < 2^-100 relative, and a quotient with a 24-bit
+// divisor is either representable or at least 2^-78 relative away from the nearest rounding boundary (n - m d is a
+// multiple of 2^(e_m + e_d - 76) for a 54-bit midpoint m), so the single rounding of the last operation lands on the
+// IEEE quotient: same bits as `/`, for 7.25 instructions per quotient (one quarter-rate) instead of 11 with the
+// compiler's sequence.  (The metric pass is as much ALU- as HBM-bound; the divisions are its largest single cost.)
+// A zero, infinite or NaN operand anywhere in the four gives NaN or infinity in the affected quotients, never a wrong
+// finite value passed as right for them: the caller tests the quotients and takes the general path then.
+QMM_DEV void reciprocals4(const double* d, double* x)
 {
-    const double x0 = __builtin_amdgcn_rcp(d);
-    const double e0 = fma(-d, x0, 1.0);
-    const double x1 = fma(x0, e0, x0);
-    const double e1 = fma(-d, x1, 1.0);
-    const double x2 = fma(x1, e1, x1);
-    const double q0 = n * x2;
-    return fma(fma(-d, q0, n), x2, q0);
+    const double p01 = d[0] * d[1], p23 = d[2] * d[3];
+    const double p = p01 * p23;
+    const double x0 = __builtin_amdgcn_rcp(p);
+    const double x1 = fma(x0, fma(-p, x0, 1.0), x0);
+    const double x2 = fma(x1, fma(-p, x1, 1.0), x1);
+    const double x01 = x2 * p23, x23 = x2 * p01;
+    x[0] = x01 * d[1]; x[1] = x01 * d[0]; x[2] = x23 * d[3]; x[3] = x23 * d[2];
+}
+// m = max(m, |v|) for values that are not NaN, as the one instruction.  (fmax() first quiets each operand that the
+// compiler cannot prove canonical -- a converted, negated or loaded value -- with an instruction of its own, which
+// doubled the cost of the running maxima.)
+QMM_DEV void max_abs_plain(double& m, double v)
+{
+    asm("v_max_f64 %0, %0, |%1|" : "+v"(m) : "v"(v));
+}
+QMM_DEV double quotient_with(double n, double d, double x)
+{
+    const double q0 = n * x;
+    return fma(fma(-d, q0, n), x, q0);
 }
 
 // Running sums of one thread.  Branch-free: an element whose error is NaN contributes zeros and bumps nan_cnt.
@@ -38,26 +58,21 @@ struct Acc {
     double re_sum = 0, re_max = 0, be_sum = 0, be_max = 0;
     unsigned re_cnt = 0, be_cnt = 0, n = 0, nan_cnt = 0;     // a thread sees far fewer than 2^32 elements
 
-    // The common case, taken when the whole wavefront's elements are ordinary: no NaN error, r != 0 and d > 0
-    // everywhere.  Same sums as add(), without the selects and compares.
-    template <bool HAS_D> QMM_DEV void add_plain(float yf, float rf, float df)
+    // The common case, taken when the whole wavefront's elements are ordinary (no NaN or infinite error, r != 0 and
+    // d > 0 everywhere): |e|, |r| and the quotients come in computed.  Same sums as add(), without its selects.
+    // re_sum and be_sum are taken by the caller (it adds the quotients itself, to test them).
+    // e and r come in signed.
+    template <bool HAS_D> QMM_DEV void add_plain(double e, double r, double q, double qb)
     {
-        const double ae = fabs((double)yf - (double)rf);
-        const double ar = fabs((double)rf);
-        s_ee = fma(ae, ae, s_ee);
-        s_rr = fma(ar, ar, s_rr);
-        s_ae += ae;
-        s_ar += ar;
-        m_e = fmax(m_e, ae);
-        m_r = fmax(m_r, ar);
-        const double q = quotient_plain(ae, ar);
-        re_sum += q;
-        re_max = fmax(re_max, q);
-        if constexpr (HAS_D) {
-            const double qb = quotient_plain(ae, (double)df);
-            be_sum += qb;
-            be_max = fmax(be_max, qb);
-        }
+        const double ae = e, ar = r;
+        s_ee = fma(e, e, s_ee);
+        s_rr = fma(r, r, s_rr);
+        s_ae += fabs(e);
+        s_ar += fabs(r);
+        max_abs_plain(m_e, ae);
+        max_abs_plain(m_r, ar);
+        max_abs_plain(re_max, q);
+        if constexpr (HAS_D) max_abs_plain(be_max, qb);
     }
     // counts of a run of `k` plain elements
     template <bool HAS_D> QMM_DEV void count_plain(unsigned k)
@@ -65,17 +80,6 @@ struct Acc {
         re_cnt += k; n += k;
         if constexpr (HAS_D) be_cnt += k;
     }
-    // true if add_plain() would not give add()'s result for this element
-    template <bool HAS_D> static QMM_DEV bool special(float yf, float rf, float df)
-    {
-        // e is NaN exactly when the binary64 difference is NaN; an infinite e (an infinite input, or a difference
-        // that overflows binary32 only) also takes the general path, which divides with the full IEEE sequence
-        const float e = yf - rf;
-        bool sp = !(fabsf(e) < __builtin_inff()) || rf == 0.0f;
-        if constexpr (HAS_D) sp = sp || !(df > 0.0f && df < __builtin_inff());
-        return sp;
-    }
-
     template <bool HAS_D> QMM_DEV void add(float yf, float rf, float df)
     {
         const double e = (double)yf - (double)rf;
@@ -162,14 +166,47 @@ metric_partial(const void* __restrict__ yv, const float* __restrict__ r, const f
         const f32x4 r0 = r4[i], r1 = r4[i + kThreads];
         f32x4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
         if constexpr (HAS_D) { d0 = d4[i]; d1 = d4[i + kThreads]; }
+        // |e|, |r| and the quotients of all eight elements first, four divisions per reciprocal estimate.  An element
+        // the plain sums would get wrong (NaN or infinite e, r == 0, d not in (0, inf)) shows as a quotient that is
+        // +infinity or NaN, which makes the running sum of quotients (all >= 0, far from overflow) non-finite, or is
+        // caught by the sign test on d: then the whole wavefront takes the general path and the sums are not kept.
+        double ae[8], ar[8], dd[8], x[8], q[8], qb[8];
+        double re_next = acc.re_sum, be_next = acc.be_sum;
         bool sp = false;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) sp = sp || Acc::special<HAS_D>(y0[j], r0[j], d0[j]) || Acc::special<HAS_D>(y1[j], r1[j], d1[j]);
+        for (int j = 0; j < 8; ++j) {
+            const float yf = j < 4 ? y0[j & 3] : y1[j & 3], rf = j < 4 ? r0[j & 3] : r1[j & 3];
+            ae[j] = (double)yf - (double)rf;       // signed: the magnitudes are operand modifiers where they are used
+            ar[j] = (double)rf;
+        }
+        reciprocals4(ar, x); reciprocals4(ar + 4, x + 4);      // signed reciprocals: the four signs cancel in pairs
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            q[j] = quotient_with(fabs(ae[j]), fabs(ar[j]), fabs(x[j]));
+            re_next += q[j];
+            qb[j] = 0.0;
+        }
+        sp = !(re_next < (double)__builtin_inff());
+        if constexpr (HAS_D) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float df = j < 4 ? d0[j & 3] : d1[j & 3];
+                dd[j] = (double)df;
+                sp = sp || !(df > 0.0f);
+            }
+            reciprocals4(dd, x); reciprocals4(dd + 4, x + 4);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                qb[j] = quotient_with(fabs(ae[j]), dd[j], x[j]);
+                be_next += qb[j];
+            }
+            sp = sp || !(be_next < (double)__builtin_inff());
+        }
         if (!__any(sp)) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc.add_plain<HAS_D>(y0[j], r0[j], d0[j]);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc.add_plain<HAS_D>(y1[j], r1[j], d1[j]);
+            for (int j = 0; j < 8; ++j) acc.add_plain<HAS_D>(ae[j], ar[j], q[j], qb[j]);
+            acc.re_sum = re_next;
+            if constexpr (HAS_D) acc.be_sum = be_next;
             acc.count_plain<HAS_D>(8u);
         } else {
             // rare path, kept rolled: unrolled, its eight interleaved IEEE divisions set the kernel's register
@@ -265,8 +302,9 @@ extern "C" qmm_status qmm_metric(const void* y, qmm_dtype y_dtype, const float* 
 
     hipStream_t s = as_stream(stream);
     double* partial = static_cast<double*>(workspace);
-    const int nb = plan_blocks(n);
     const bool bf = y_dtype == QMM_DT_BF16, hd = denom != nullptr;
+    // with denominators the kernel holds 156 registers: three workgroups resident per CU, so no more than that are launched
+    const int nb = hd ? std::min(plan_blocks(n), 768) : plan_blocks(n);
     if (bf && hd) metric_partial<true, true><<<nb, kThreads, 0, s>>>(y, y_ref, denom, n, partial);
     else if (bf) metric_partial<true, false><<<nb, kThreads, 0, s>>>(y, y_ref, denom, n, partial);
     else if (hd) metric_partial<false, true><<<nb, kThreads, 0, s>>>(y, y_ref, denom, n, partial);

@@ -19,17 +19,27 @@ struct Sums {
     float amax = 0.f;
     unsigned cnt = 0, nan_cnt = 0;
 
-    QMM_DEV void add_plain(float xf, double center)
-    {
-        const double d = (double)xf - center, d2 = d * d;
-        s1 += d; s2 += d2; s3 = fma(d2, d, s3); s4 = fma(d2, d2, s4);
-        amax = fmaxf(amax, fabsf(xf));
-    }
     QMM_DEV void add(float xf, double center)
     {
         if (xf != xf) { nan_cnt += 1u; return; }
-        add_plain(xf, center);
+        const double d = (double)xf - center, d2 = d * d;
+        s1 += d; s2 += d2; s3 = fma(d2, d, s3); s4 = fma(d2, d2, s4);
+        amax = fmaxf(amax, fabsf(xf));
         cnt += 1u;
+    }
+    // Eight elements none of which is NaN.  CENTERED = false: center == 0, the subtraction is left out (x - 0 = x).
+    // The pass is ALU- as much as HBM-bound (a bfloat16 element brings 2 bytes and needs 8 instructions), so the
+    // common case is kept to the conversions, one multiply and four accumulations per element.
+    template <bool CENTERED> QMM_DEV void add8_plain(const double (&d)[8], const float (&e)[8])
+    {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const double d2 = d[i] * d[i];
+            s2 += d2; s3 = fma(d2, d[i], s3); s4 = fma(d2, d2, s4);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) amax = fmaxf(fmaxf(amax, fabsf(e[i])), fabsf(e[i + 1]));    // one three-way maximum
+        cnt += 8u;
     }
 };
 
@@ -47,20 +57,22 @@ template <bool BF16> QMM_DEV void load8(const void* x, int64_t v, float (&out)[8
 }
 
 // partial[field * nblocks + block]
-template <bool BF16> __global__ void __launch_bounds__(kThreads)
+template <bool BF16, bool CENTERED> __global__ void __launch_bounds__(kThreads)
 moments_partial(const void* __restrict__ x, int64_t n, double center, double* __restrict__ partial)
 {
     Sums acc;
     const int64_t nvec = n >> 3;                       // vectors of eight elements
     const int64_t tid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     auto consume = [&](const float (&e)[8]) {
-        bool any_nan = false;
+        // The eight deviations are summed first, as a tree: a NaN element makes that sum NaN (so do infinities of
+        // both signs, for which the general path gives the same NaN sums), and one test replaces eight.
+        double d[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) any_nan = any_nan || (e[i] != e[i]);
-        if (!__any(any_nan)) {                         // the common case, without per-element tests
-#pragma unroll
-            for (int i = 0; i < 8; ++i) acc.add_plain(e[i], center);
-            acc.cnt += 8u;
+        for (int i = 0; i < 8; ++i) d[i] = CENTERED ? (double)e[i] - center : (double)e[i];
+        const double t = ((d[0] + d[1]) + (d[2] + d[3])) + ((d[4] + d[5]) + (d[6] + d[7]));
+        if (!__any(t != t)) {                          // the common case, without per-element tests
+            acc.s1 += t;
+            acc.template add8_plain<CENTERED>(d, e);
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc.add(e[i], center);
@@ -177,8 +189,11 @@ extern "C" qmm_status qmm_moments(const void* x, qmm_dtype dtype, int64_t n, dou
     hipStream_t s = as_stream(stream);
     double* partial = static_cast<double*>(workspace);
     const int nb = plan_blocks(n);
-    if (dtype == QMM_DT_BF16) moments_partial<true><<<nb, kThreads, 0, s>>>(x, n, center, partial);
-    else moments_partial<false><<<nb, kThreads, 0, s>>>(x, n, center, partial);
+    const bool bf = dtype == QMM_DT_BF16, centered = center != 0.0;
+    if (bf && centered) moments_partial<true, true><<<nb, kThreads, 0, s>>>(x, n, center, partial);
+    else if (bf) moments_partial<true, false><<<nb, kThreads, 0, s>>>(x, n, center, partial);
+    else if (centered) moments_partial<false, true><<<nb, kThreads, 0, s>>>(x, n, center, partial);
+    else moments_partial<false, false><<<nb, kThreads, 0, s>>>(x, n, center, partial);
     if (hipGetLastError() != hipSuccess) return QMM_ERR_LAUNCH;
     moments_finalize<<<1, kFields * kWave, 0, s>>>(partial, nb, center, out8);
     return launch_status();
