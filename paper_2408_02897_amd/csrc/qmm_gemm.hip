@@ -35,6 +35,7 @@
 //    Outputs at most 64 wide or high: gemm_direct_kernel (no LDS).
 #include <type_traits>
 
+#include <cstdlib>
 #include "qmm_device.h"
 
 namespace qmm {
@@ -1034,6 +1035,362 @@ gemm_shortk_kernel(GemmArgs g)
     }
 }
 
+// Several 256 x 256 tiles per CU and a contraction of three slabs or more (the linear layers of a transformer).
+// With gemm_kernel every tile pays a fixed price that no matrix instruction covers: the first copies' latency, and
+// above all its 128 KB of stores, which all CUs issue at the same moment (8-9 us per tile at K = 1024, where the
+// matrix work itself takes 11 us).  Here the workgroup stays on its CU and the slabs of all its tiles form ONE
+// stream through the same LDS ring (three slots of A, two of B) with the same step schedule as gemm_kernel: at a
+// tile's last steps the slabs requested are simply the first ones of the next tile, so the next tile's first step
+// starts right behind the epilogue, and the stores drain while it runs.
+// Vector-memory operations complete in order, loads and stores alike, so "slab q+1 has landed" is "at most n newer
+// operations outstanding".  At a tile boundary the copies that the next tile's first step would request before its
+// barrier are requested in front of the stores instead; that step then requests none and waits with the exact number
+// of stores allowed outstanding, and the stores are only waited for one step later (they have had 2-3 us by then).
+// Codes in, whole tiles, whole slabs, no split, output in y alone; same fragment, accumulator and store layout as
+// gemm_kernel.
+template <int KIND, int FA, int FB>
+__global__ void __launch_bounds__(512, 1)
+gemm_stream_kernel(GemmArgs g)
+{
+    constexpr bool F8 = (KIND == KIND_F8);
+    constexpr int NWN = 4, NWAVES = 8;
+    constexpr int BM = 256, BN = 256, WM = 128, WN = 64;
+    constexpr int R = F8 ? 16 : 32;
+    constexpr int BLOCKS_M = WM / R, TILES_N = WN / R;
+    constexpr int KS = F8 ? 1 : 4;
+    constexpr int REGS = F8 ? 4 : 16;
+    constexpr int A_SLOT = BM * kSlabBytes, B_SLOT = BN * kSlabBytes;
+    constexpr int B_BASE = kASlots * A_SLOT;
+    constexpr int NA = BM / 8 / NWAVES, NB = BN / 8 / NWAVES;      // copies per wavefront and slab
+    constexpr int NB_TAIL = NB / 2;
+    constexpr int MMAS_PER_BLOCK = KS * TILES_N;
+    constexpr int N1 = (BLOCKS_M - 1) * MMAS_PER_BLOCK;
+    constexpr int NC = (NB - NB_TAIL) + NA;
+    constexpr int STORES = BLOCKS_M * REGS;                        // of one tile's epilogue: one per row and lane
+    constexpr int STORES_W = STORES > 63 ? 63 : STORES;            // (the counter has six bits: waiting for more is safe)
+    static_assert(kASlots == 3 && kBSlots == 2, "slot arithmetic below");
+    static_assert(NC <= N1 && NB_TAIL <= MMAS_PER_BLOCK, "one copy per MFMA at most");
+    using AccT = typename std::conditional<F8, v4f, v16i>::type;
+    using Frag = typename std::conditional<F8, v8i, v4i>::type;
+    static_assert(KIND == KIND_F8 || KIND == KIND_I8, "8-bit codes only");
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / NWN, wn = wave % NWN;
+    const int rowbytes = (int)g.rowbytes;
+    const int nk = rowbytes / kSlabBytes;                          // >= 3, exact (host)
+    const uint32_t tiles_per_batch = (uint32_t)g.tiles_m * (uint32_t)g.tiles_n;
+    const uint32_t total = tiles_per_batch * (uint32_t)g.batch;
+
+    // ---- copy sources (32-bit byte offsets from a tile's first A / B row) and LDS targets, as in gemm_kernel
+    uint32_t a_src[NA], b_src[NB];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int p = (wave * NA + i) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((p >> 1) & 7);
+        a_src[i] = (uint32_t)(p * rowbytes + c * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int p = (wave * NB + i) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((p >> 1) & 7);
+        const int row = WN * (p / WN) + TILES_N * (p % R) + (p / R) % TILES_N;
+        b_src[i] = (uint32_t)(row * rowbytes + c * 16);
+    }
+    typedef __attribute__((address_space(3))) uint8_t* lds_ptr_t;
+    const uint32_t lds_a_units = (uint32_t)(uintptr_t)(lds_ptr_t)(lds + wave * NA * 1024);
+    const uint32_t lds_b_units = (uint32_t)(uintptr_t)(lds_ptr_t)(lds + B_BASE + wave * NB * 1024);
+    auto copy_a = [&](const uint8_t* slab, int i, int slot) { dma16_uniform(slab, a_src[i], lds_a_units + slot * A_SLOT + i * 1024); };
+    auto copy_b = [&](const uint8_t* slab, int i, int slot) { dma16_uniform(slab, b_src[i], lds_b_units + slot * B_SLOT + i * 1024); };
+
+    // workgroup-wide tile number -> tile, with gemm_kernel's mapping (XCD-aware, grouped along m); the tiles of one
+    // workgroup (numbers blockIdx.x + i * gridDim.x, the grid a multiple of the XCD count) stay within its XCD's range
+    struct Tile { const uint8_t* a; const uint8_t* b; int64_t bidx, m0, n0; };
+    auto tile_of = [&](uint32_t pid) -> Tile {
+        const uint32_t per = (total + kNumXcd - 1) / kNumXcd, tall = total % kNumXcd;
+        const uint32_t xcd = pid % kNumXcd, loc = pid / kNumXcd;
+        pid = (tall == 0 || xcd < tall) ? xcd * per + loc : tall * per + (xcd - tall) * (per - 1) + loc;
+        const int64_t bidx = __builtin_amdgcn_readfirstlane((int)(pid / tiles_per_batch));
+        const uint32_t t = pid - (uint32_t)bidx * tiles_per_batch;
+        constexpr uint32_t GROUP_M = 8;
+        const uint32_t in_group = GROUP_M * (uint32_t)g.tiles_n;
+        const uint32_t grp = t / in_group;
+        const uint32_t first_m = grp * GROUP_M;
+        const uint32_t gsz = min(GROUP_M, (uint32_t)g.tiles_m - first_m);
+        const int64_t tile_m = __builtin_amdgcn_readfirstlane((int)(first_m + (t - grp * in_group) % gsz));
+        const int64_t tile_n = __builtin_amdgcn_readfirstlane((int)((t - grp * in_group) / gsz));
+        Tile o;
+        o.bidx = bidx; o.m0 = tile_m * BM; o.n0 = tile_n * BN;
+        o.a = g.a + (bidx * g.M + o.m0) * g.rowbytes;
+        o.b = g.b + (bidx * g.N + o.n0) * g.rowbytes;
+        return o;
+    };
+
+    // ---- fragments and matrix instructions (as in gemm_kernel)
+    const int frow = lane & (R - 1);
+    const int fkey = (frow >> 1) & 7;
+    const int fsel = F8 ? (lane >> 4) : (lane >> 5);
+    const int a_off = (wm * WM + frow) * kSlabBytes;
+    const int b_off = B_BASE + (wn * WN + frow) * kSlabBytes;
+    int coff[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) coff[s] = ((F8 ? fsel : 2 * s + fsel) ^ fkey) * 16;
+    auto read_frag = [&](const uint8_t* row_ptr, int s) -> Frag {
+        if constexpr (F8) {
+            const v4i p0 = *reinterpret_cast<const v4i*>(row_ptr + coff[0]);
+            const v4i p1 = *reinterpret_cast<const v4i*>(row_ptr + (coff[0] ^ 64));
+            return v8i{p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
+        } else {
+            return *reinterpret_cast<const v4i*>(row_ptr + coff[s]);
+        }
+    };
+    // FIRST (a tile's first slab): the product alone, with the constant 0 as the addend, written to the accumulator
+    // block as a fresh value.  So the accumulators are never initialised by separate instructions (whose 128 zeros
+    // passed through vector registers next to the live fragments) and no value of theirs is carried around the loop.
+    auto mma = [&](const Frag& fa, const Frag& fb, AccT& c, auto first_tag) {
+        constexpr bool FIRST = decltype(first_tag)::value;
+#if defined(__HIP_DEVICE_COMPILE__)
+        if constexpr (FIRST) {
+            if constexpr (F8) {
+                if constexpr (FA == QMM_FMT_E5M2 && FB == QMM_FMT_E5M2)
+                    asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, 0 cbsz:1 blgp:1" : "=a"(c) : "v"(fa), "v"(fb));
+                else if constexpr (FA == QMM_FMT_E5M2)
+                    asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, 0 cbsz:1" : "=a"(c) : "v"(fa), "v"(fb));
+                else if constexpr (FB == QMM_FMT_E5M2)
+                    asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, 0 blgp:1" : "=a"(c) : "v"(fa), "v"(fb));
+                else
+                    asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, 0" : "=a"(c) : "v"(fa), "v"(fb));
+            } else {
+                asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, 0" : "=a"(c) : "v"(fa), "v"(fb));
+            }
+        } else {
+            if constexpr (F8) {
+                if constexpr (FA == QMM_FMT_E5M2 && FB == QMM_FMT_E5M2)
+                    asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 cbsz:1 blgp:1" : "+a"(c) : "v"(fa), "v"(fb));
+                else if constexpr (FA == QMM_FMT_E5M2)
+                    asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 cbsz:1" : "+a"(c) : "v"(fa), "v"(fb));
+                else if constexpr (FB == QMM_FMT_E5M2)
+                    asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 blgp:1" : "+a"(c) : "v"(fa), "v"(fb));
+                else
+                    asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(c) : "v"(fa), "v"(fb));
+            } else {
+                asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+a"(c) : "v"(fa), "v"(fb));
+            }
+        }
+#endif
+    };
+    AccT acc[BLOCKS_M][TILES_N];
+    Frag fb[KS][TILES_N];      // B fragments of the current slab
+    Frag fa[2][KS];            // A fragments of one block, ping-pong between blocks
+    auto read_a = [&](int slot, int i, int buf) {
+        const uint8_t* sa = lds + slot * A_SLOT + a_off + i * R * kSlabBytes;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) fa[buf][s] = read_frag(sa, s);
+    };
+
+    const uint32_t stride = gridDim.x;
+    uint32_t t_cur = blockIdx.x;
+    if (t_cur >= total) return;
+    Tile cur = tile_of(t_cur);
+
+    // ---- prologue of the stream: slab 0 of both operands, then what the steps before a tile's first step request
+    // for it (A slab 1, B slab 1) and what is requested in front of the stores at a tile boundary (A slab 2)
+#pragma unroll
+    for (int i = 0; i < NA; ++i) copy_a(cur.a, i, 0);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) copy_b(cur.b, i, 0);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) copy_a(cur.a + kSlabBytes, i, 1);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) copy_b(cur.b + kSlabBytes, i, 1);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) copy_a(cur.a + 2 * kSlabBytes, i, 2);
+    wait_vm<NA + NB + NA>();
+    __syncthreads();
+    {
+        const uint8_t* sb = lds + b_off;
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int j = 0; j < TILES_N; ++j) fb[s][j] = read_frag(sb + j * R * kSlabBytes, s);
+    }
+    read_a(0, 0, 0);
+    // The two step sizes (one per operand: the host sends other granularities to gemm_kernel), fetched here and moved
+    // to scalar registers at once: inside the loop there is then no load the compiler knows of, only stores -- with
+    // both kinds outstanding it places full waits (vmcnt(0)) in front of the first use of a loaded register, and on
+    // the way round the loop such a wait landed in the first step of every tile, behind all of the stores.
+    const float delta_a = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, g.da[0])));
+    const float delta_b = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, g.db[0])));
+
+    int a_slot = 0, b_slot = 0;                // ring slots of the stream's current slab
+    for (;;) {
+        const uint32_t t_next = t_cur + stride;
+        const bool has_next = t_next < total;
+        const Tile nxt = has_next ? tile_of(t_next) : cur;
+
+        // One step of the stream (slab kt of the current tile).  The slabs after it are the current tile's, or the
+        // first ones of the next tile.  STEADY: slabs +1 and +2 exist, every copy is requested without a test.
+        // START: a tile's first step: its copies were requested in front of the stores of the tile before (in the
+        // prologue for the first tile), and its matrix instructions start the accumulators.
+        // (One chain of steps per tile, without alternatives: where the flow of control split over whole steps, the
+        // accumulator blocks that met again behind them were moved through vector registers and memory.)
+        auto step = [&](int kt, auto steady_tag, auto start_tag) {
+            constexpr bool STEADY = decltype(steady_tag)::value, START = decltype(start_tag)::value;
+            constexpr bool START_OR_FIRST = START;
+            const bool in1 = kt + 1 < nk, in2 = kt + 2 < nk;
+            const bool more = STEADY || has_next || in1, more2 = STEADY || has_next || in2;
+            const uint8_t* pb1 = in1 ? cur.b + (kt + 1) * kSlabBytes : nxt.b + (kt + 1 - nk) * kSlabBytes;
+            const uint8_t* pa2 = in2 ? cur.a + (kt + 2) * kSlabBytes : nxt.a + (kt + 2 - nk) * kSlabBytes;
+            const uint8_t* pb2 = in2 ? cur.b + (kt + 2) * kSlabBytes : nxt.b + (kt + 2 - nk) * kSlabBytes;
+            const int a_next = a_slot == 2 ? 0 : a_slot + 1;
+            const int a_free = a_slot == 0 ? 2 : a_slot - 1;
+            auto copy_before_e = [&](int c) {
+                if (c < NB - NB_TAIL) { if (more) copy_b(pb1, NB_TAIL + c, b_slot ^ 1); }
+                else { if (more2) copy_a(pa2, c - (NB - NB_TAIL), a_free); }
+            };
+#pragma unroll
+            for (int i = 0; i < BLOCKS_M - 1; ++i) {
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+#pragma unroll
+                    for (int j = 0; j < TILES_N; ++j) {
+                        const int q = s * TILES_N + j;
+                        const int m = i * MMAS_PER_BLOCK + q;
+                        if (START_OR_FIRST && s == 0) mma(fa[i & 1][s], fb[s][j], acc[i][j], std::true_type{});
+                        else mma(fa[i & 1][s], fb[s][j], acc[i][j], std::false_type{});
+                        if (q == 0) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            read_a(a_slot, i + 1, (i + 1) & 1);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        if constexpr (!START) {
+#pragma unroll
+                            for (int c = 0; c < NC; ++c)
+                                if ((c * N1) / NC == m) {
+                                    __builtin_amdgcn_sched_barrier(0);
+                                    copy_before_e(c);
+                                    __builtin_amdgcn_sched_barrier(0);
+                                }
+                        }
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (more) {
+                // E: every LDS read of this slab has completed and the next slab has landed
+                if constexpr (START) {
+                    // the newest operations are the stores of the tile before; for the first tile, the copies of A slab 2
+                    if (t_cur == blockIdx.x) wait_vm_lgkm<NA>(); else wait_vm_lgkm<STORES_W>();
+                } else {
+                    if (more2) wait_vm_lgkm<NA>(); else wait_vm_lgkm<0>();
+                }
+                __syncthreads();
+                read_a(a_next, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            const uint8_t* sb_next = lds + (b_slot ^ 1) * B_SLOT + b_off;
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+#pragma unroll
+                for (int j = 0; j < TILES_N; ++j) {
+                    const int q = s * TILES_N + j;
+                    if (START_OR_FIRST && s == 0) mma(fa[(BLOCKS_M - 1) & 1][s], fb[s][j], acc[BLOCKS_M - 1][j], std::true_type{});
+                    else mma(fa[(BLOCKS_M - 1) & 1][s], fb[s][j], acc[BLOCKS_M - 1][j], std::false_type{});
+                    if (more) fb[s][j] = read_frag(sb_next + j * R * kSlabBytes, s);
+#pragma unroll
+                    for (int c = 0; c < NB_TAIL; ++c)
+                        if ((c * MMAS_PER_BLOCK) / NB_TAIL == q) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (more2) copy_b(pb2, c, b_slot);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            a_slot = a_next;
+            b_slot ^= 1;
+        };
+        using T = std::true_type; using F = std::false_type;
+        step(0, T{}, T{});
+        for (int kt = 1; kt < nk - 2; ++kt) step(kt, T{}, F{});
+        step(nk - 2, F{}, F{});
+        step(nk - 1, F{}, F{});
+
+        if (has_next) {
+            // what the next tile's first step would request before its barrier: the second half of its B slab 1 and
+            // its A slab 2 (a_slot, b_slot now belong to its slab 0)
+            const int a_free = a_slot == 0 ? 2 : a_slot - 1;
+#pragma unroll
+            for (int c = 0; c < NB - NB_TAIL; ++c) copy_b(nxt.b + kSlabBytes, NB_TAIL + c, b_slot ^ 1);
+#pragma unroll
+            for (int i = 0; i < NA; ++i) copy_a(nxt.a + 2 * kSlabBytes, i, a_free);
+        }
+        // wait states between the last matrix instruction and the first read of an accumulator
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- epilogue of a whole tile: (acc * deltaA) * deltaB, in that order
+        {
+            const int64_t m_base = cur.m0 + wm * WM, n_base = cur.n0 + wn * WN;
+            int lane_e = lane;                    // kept out of the loop-invariant code the compiler would hoist
+            asm volatile("" : "+v"(lane_e));
+            const int64_t n = n_base + TILES_N * (lane_e & (R - 1));
+            const int lane_row = F8 ? 4 * (lane_e >> 4) : 4 * (lane_e >> 5);
+            auto row_in_block = [&](int r) -> int { return F8 ? lane_row + r : 8 * (r >> 2) + lane_row + (r & 3); };
+            auto value = [&](int ia, int r, int tt) -> float {
+                uint32_t raw;
+                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(raw) : "a"(acc[ia][tt][r]));
+                float a;
+                if constexpr (KIND == KIND_I8) a = (float)(int32_t)raw;
+                else a = __uint_as_float(raw);
+                return (a * delta_a) * delta_b;
+            };
+            if (g.y_bf16) {
+                uint8_t* ybase = static_cast<uint8_t*>(g.y) + ((cur.bidx * g.M + m_base) * g.N + n) * 2;
+                const int64_t row_bytes = g.N * 2;
+                typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+                typedef float f2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+                for (int ia = 0; ia < BLOCKS_M; ++ia) {
+#pragma unroll
+                    for (int r = 0; r < REGS; ++r) {
+                        uint32_t pk[TILES_N / 2];
+#pragma unroll
+                        for (int q = 0; q < TILES_N / 2; ++q) {
+                            const float v0 = value(ia, r, 2 * q), v1 = value(ia, r, 2 * q + 1);
+                            pk[q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{v0, v1}, bf2));
+                        }
+                        uint8_t* dst = ybase + (ia * R + row_in_block(r)) * row_bytes;
+                        if constexpr (TILES_N == 4) *reinterpret_cast<u32x2*>(dst) = u32x2{pk[0], pk[1]};
+                        else *reinterpret_cast<uint32_t*>(dst) = pk[0];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+                float* ybase = static_cast<float*>(g.y) + (cur.bidx * g.M + m_base) * g.N + n;
+#pragma unroll
+                for (int ia = 0; ia < BLOCKS_M; ++ia) {
+#pragma unroll
+                    for (int r = 0; r < REGS; ++r) {
+                        float* dst = ybase + (int64_t)(ia * R + row_in_block(r)) * g.N;
+                        if constexpr (TILES_N == 4) {
+                            v4f v;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] = value(ia, r, e);
+                            *reinterpret_cast<v4f*>(dst) = v;
+                        } else {
+                            typedef float f2 __attribute__((ext_vector_type(2)));
+                            *reinterpret_cast<f2*>(dst) = f2{value(ia, r, 0), value(ia, r, 1)};
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        if (!has_next) break;
+        cur = nxt; t_cur = t_next;
+    }
+}
+
 // An output at most 64 wide or high (attention: probabilities x values, N = head dimension) makes the product
 // HBM-bound: the long operand is read exactly once and nothing of it is reused, so staging it in LDS buys nothing,
 // while a 128 x 128 tile wastes half its columns and its ring admits two workgroups per CU at most.  Here a
@@ -1389,6 +1746,35 @@ qmm_status launch_shortk(GemmArgs& g, hipStream_t s)
     return launch_status();
 }
 
+// gemm_stream_kernel: codes in with one step size per operand, no split, whole 256 x 256 tiles, whole slabs and at
+// least three of them, output in y alone, and more tiles than workgroups in the grid (with one tile each there is nothing to overlap).
+constexpr int kStreamGrid = 256;
+bool use_stream(const GemmArgs& g, int fuse)
+{
+    if (fuse != 0 || g.splits > 1 || g.rowbytes % kSlabBytes != 0 || g.rowbytes < 3 * kSlabBytes) return false;
+    if (g.M % 256 != 0 || g.N % 256 != 0 || !g.y || g.acc_out) return false;
+    if (g.da_per_channel || g.db_per_channel || g.da_groups != 1 || g.db_groups != 1) return false;   // one step size per operand
+    return (g.M / 256) * (g.N / 256) * g.batch > kStreamGrid;
+}
+
+template <int KIND, int FA, int FB>
+qmm_status launch_stream(GemmArgs& g, hipStream_t s)
+{
+    constexpr int LDS_BYTES = (kASlots + kBSlots) * 256 * kSlabBytes;
+    g.tiles_m = (int)(g.M / 256);
+    g.tiles_n = (int)(g.N / 256);
+    if ((int64_t)g.tiles_m * g.tiles_n * g.batch > 0x7FFFFFFF) return QMM_ERR_UNSUPPORTED;
+    auto kern = gemm_stream_kernel<KIND, FA, FB>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+            return QMM_ERR_LAUNCH;
+        attr_set = true;
+    }
+    kern<<<kStreamGrid, 512, LDS_BYTES, s>>>(g);
+    return launch_status();
+}
+
 template <int KIND, int FA, int FB, int FUSE>
 qmm_status launch_fuse(GemmArgs& g, hipStream_t s)
 {
@@ -1403,6 +1789,7 @@ qmm_status launch_fuse(GemmArgs& g, hipStream_t s)
     if constexpr (FUSE == 0) {
         if (use_direct(g, 0)) return launch_direct<KIND, FA, FB>(g, s);
         if (use_shortk<KIND>(g, 0)) return launch_shortk<KIND, FA, FB>(g, s);
+        if constexpr (KIND != KIND_BF16) { if (use_stream(g, 0)) return launch_stream<KIND, FA, FB>(g, s); }
     }
     // 256 x 256 tiles (eight wavefronts, two per SIMD: while one waits at a copy or a fragment read the other
     // issues matrix instructions) when they still give every CU work, else 128 x 128 tiles (four wavefronts, two

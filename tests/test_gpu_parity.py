@@ -277,6 +277,42 @@ def test_gemm_fp8_within_tolerance(shape, fa, fb):
     assert np.array_equal(y.cpu().numpy().view(np.uint32), want_y.view(np.uint32))
 
 
+# more 256 x 256 tiles than CUs, whole slabs, three at least, one step size per operand, output in y alone: the kernel
+# whose workgroups stream their tiles' slabs through one ring.  Three slabs (no step in the steady loop) with some
+# workgroups taking two tiles and others one; a batch; eight slabs and two to three tiles per workgroup.
+STREAM_SHAPES = [(1, 4352, 4352, 384), (3, 2560, 2560, 640), (1, 8192, 5120, 1024)]
+
+
+@pytest.mark.parametrize("shape", STREAM_SHAPES)
+@pytest.mark.parametrize("fa,fb", [(qmm.INT8, qmm.INT8), (qmm.E4M3, qmm.E4M3), (qmm.E5M2, qmm.E4M3), (qmm.E4M3, qmm.E5M2)])
+def test_gemm_streaming_kernel(shape, fa, fb):
+    """Accumulators (from the call that returns them) against the oracle on sampled rows of every matrix -- first and
+    last row, rows around tile borders -- then the y-only calls: every element equal to the oracle's descale of those
+    accumulators (binary32 and bfloat16 out)."""
+    bt, M, N, K = shape
+    a = _random_codes(fa, (bt, M, K), 7); b = _random_codes(fb, (bt, N, K), 8)
+    ta, tb = torch.from_numpy(a).to(DEV), torch.from_numpy(b).to(DEV)
+    da = np.array([3.7e-3], np.float32); db = np.array([9.1e-3], np.float32)
+    oa = qmm.operand(ta, fa, torch.from_numpy(da).to(DEV), False); ob = qmm.operand(tb, fb, torch.from_numpy(db).to(DEV), False)
+    _, acc = qmm.gemm((ta, oa), (tb, ob), torch.float32, want_acc=True)
+    acc = acc.cpu().numpy()
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, 257, M - 257, M - 256, M - 1],
+                                     np.random.default_rng(M + K).choice(M, 16, replace=False)]))
+    if fa == qmm.INT8:
+        assert np.array_equal(acc[:, rows].astype(np.int64), O.gemm_int8(a[:, rows], b))
+    else:
+        for m in range(bt):
+            want, sabs = O.gemm_codes_rows(a[m], fa, b[m], fb, rows)
+            err = np.abs(acc[m][rows].astype(np.float64) - want)
+            bound = hw_fp8_bound(a[m:m + 1, rows], fa, b[m:m + 1], fb, sabs[None])[0]
+            assert np.all(err <= bound), f"matrix {m}: err/bound {np.max(err / (bound + 1e-300)):.3f}"
+    for out_dtype, out_bf16 in ((torch.float32, False), (torch.bfloat16, True)):
+        y = qmm.gemm((ta, oa), (tb, ob), out_dtype)
+        for m in range(bt):          # a matrix at a time: the oracle's descale works in binary64 copies
+            want_y = O.dequant(acc[m:m + 1].astype(np.float64), da, db, False, 1, False, 1, out_bf16)
+            assert np.array_equal(np32(y[m:m + 1]).view(np.uint32), want_y.view(np.uint32)), (m, out_dtype)
+
+
 def test_gemm_fp8_exact_cases():
     """Powers of two and one-hot inputs give exact binary32 sums in any order."""
     M, N, K = 144, 80, 384
