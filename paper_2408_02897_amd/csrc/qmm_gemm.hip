@@ -1227,7 +1227,7 @@ gemm_stream_kernel(GemmArgs g)
     for (;;) {
         const uint32_t t_next = t_cur + stride;
         const bool has_next = t_next < total;
-        const Tile nxt = has_next ? tile_of(t_next) : cur;
+        Tile nxt = cur;        // set behind the tile's first step (first wanted two steps before the tile's end)
 
         // One step of the stream (slab kt of the current tile).  The slabs after it are the current tile's, or the
         // first ones of the next tile.  STEADY: slabs +1 and +2 exist, every copy is requested without a test.
@@ -1311,6 +1311,9 @@ gemm_stream_kernel(GemmArgs g)
         };
         using T = std::true_type; using F = std::false_type;
         step(0, T{}, T{});
+        // the next tile's coordinates: a few hundred scalar and vector instructions (divisions), here behind matrix
+        // instructions already issued rather than between the epilogue and the first of them
+        if (has_next) nxt = tile_of(t_next);
         for (int kt = 1; kt < nk - 2; ++kt) step(kt, T{}, F{});
         step(nk - 2, F{}, F{});
         step(nk - 1, F{}, F{});
