@@ -33,6 +33,10 @@
 //    tiles.
 //  * Long K with few tiles: split-K with a second, fixed-order reduction kernel.
 //    Outputs at most 64 wide or high: gemm_direct_kernel (no LDS).
+//    Contractions of one slab at most with many whole tiles: gemm_shortk_kernel;
+//    several whole tiles per CU and one step size per operand: gemm_stream_kernel
+//    (both: workgroups that stay on their CU and overlap a tile's stores with the
+//    next tile's work).
 #include <type_traits>
 
 #include <cstdlib>
