@@ -45,14 +45,16 @@ def check_asm():
     matrix instructions and copies: (1) no accumulator register is written by v_accvgpr_write within six
     instructions in front of an MFMA that uses it (wait states), (2) every LDS copy has its base address in scalar
     registers, (3) no MFMA goes through v_accvgpr_mov copies inside the loops (at most one initialisation pass), (4) the
-    kernels on the throughput path use no scratch memory.  Returns a list of findings (empty = clean)."""
+    kernels on the throughput path use no scratch memory, (5) the streaming kernel initialises no accumulator by a
+    separate instruction and has no load the compiler knows of behind its first MFMA (with stores outstanding the
+    compiler waits for such a load with vmcnt(0), i.e. for every store).  Returns a list of findings (empty = clean)."""
     os.makedirs(OBJDIR, exist_ok=True)
     asm = os.path.join(OBJDIR, "qmm_gemm.s")
     subprocess.run([HIPCC, *[f for f in FLAGS if f != "-fPIC"], "--cuda-device-only", "-S",
                     os.path.join(CSRC, "qmm_gemm.hip"), "-o", asm], check=True)
     text = open(asm).read()
     findings = []
-    names = list(dict.fromkeys(re.findall(r"^(_ZN3qmm\S*(?:gemm_kernel|gemm_shortk_kernel)\S*):", text, flags=re.M)))
+    names = list(dict.fromkeys(re.findall(r"^(_ZN3qmm\S*(?:gemm_kernel|gemm_shortk_kernel|gemm_stream_kernel)\S*):", text, flags=re.M)))
     for nm in names:
         start = text.index("\n" + nm + ":")
         end = text.index(".Lfunc_end", start)
@@ -71,6 +73,13 @@ def check_asm():
         for off, base in re.findall(r"global_load_lds_dwordx4 (\S+) (\S+)", body):
             if not base.startswith("s["):
                 findings.append(f"{nm}: LDS copy with a vector base address ({off} {base})")
+        if "gemm_stream_kernel" in nm:
+            first = next((k for k, l in enumerate(instrs) if l.startswith("v_mfma")), len(instrs))
+            late = [l for l in instrs[first:] if re.match(r"(global|flat|buffer|scratch)_load_(?!lds)", l)]
+            if late:
+                findings.append(f"{nm}: {len(late)} loads behind the first MFMA, e.g. '{late[0][:60]}'")
+            if body.count("v_accvgpr_write") or body.count("v_accvgpr_mov"):
+                findings.append(f"{nm}: accumulators written or moved by separate instructions")
         n_acc = 128 if ("ELi4ELi1ELi4E" in nm or "shortk" in nm) else 64
         if body.count("v_accvgpr_mov") > n_acc:
             findings.append(f"{nm}: {body.count('v_accvgpr_mov')} v_accvgpr_mov (accumulators copied around MFMAs)")
@@ -80,7 +89,7 @@ def check_asm():
         fuse = int(re.findall(r"Li(\d+)E", targs.group(1))[6]) if targs else 0      # <KIND, FA, FB, TM, TG, NWN, FUSE, NSR>
         if sc and int(sc.group(1)) > 0 and targs and fuse == 0:                       # codes-in kernels: the throughput path
             findings.append(f"{nm}: {sc.group(1)} bytes of scratch per lane")
-        if sc and int(sc.group(1)) > 0 and "shortk" in nm:
+        if sc and int(sc.group(1)) > 0 and ("shortk" in nm or "gemm_stream_kernel" in nm):
             findings.append(f"{nm}: {sc.group(1)} bytes of scratch per lane")
     return names, findings
 
