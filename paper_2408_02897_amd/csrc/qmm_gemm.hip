@@ -1212,14 +1212,6 @@ gemm_stream_kernel(GemmArgs g)
     for (int i = 0; i < NA; ++i) copy_a(cur.a + 2 * kSlabBytes, i, 2);
     wait_vm<NA + NB + NA>();
     __syncthreads();
-    {
-        const uint8_t* sb = lds + b_off;
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-#pragma unroll
-            for (int j = 0; j < TILES_N; ++j) fb[s][j] = read_frag(sb + j * R * kSlabBytes, s);
-    }
-    read_a(0, 0, 0);
     // The two step sizes (one per operand: the host sends other granularities to gemm_kernel), fetched here and moved
     // to scalar registers at once: inside the loop there is then no load the compiler knows of, only stores -- with
     // both kinds outstanding it places full waits (vmcnt(0)) in front of the first use of a loaded register, and on
@@ -1232,6 +1224,17 @@ gemm_stream_kernel(GemmArgs g)
         const uint32_t t_next = t_cur + stride;
         const bool has_next = t_next < total;
         Tile nxt = cur;        // set behind the tile's first step (first wanted two steps before the tile's end)
+        // The fragments of the tile's first slab are read here, not at the end of the tile before (its last step's
+        // barrier made them available): across the epilogue they would hold 48 registers that it needs.
+        {
+            const uint8_t* sb = lds + b_slot * B_SLOT + b_off;
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+#pragma unroll
+                for (int j = 0; j < TILES_N; ++j) fb[s][j] = read_frag(sb + j * R * kSlabBytes, s);
+        }
+        read_a(a_slot, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
 
         // One step of the stream (slab kt of the current tile).  The slabs after it are the current tile's, or the
         // first ones of the next tile.  STEADY: slabs +1 and +2 exist, every copy is requested without a test.
@@ -1239,8 +1242,9 @@ gemm_stream_kernel(GemmArgs g)
         // prologue for the first tile), and its matrix instructions start the accumulators.
         // (One chain of steps per tile, without alternatives: where the flow of control split over whole steps, the
         // accumulator blocks that met again behind them were moved through vector registers and memory.)
-        auto step = [&](int kt, auto steady_tag, auto start_tag) {
+        auto step = [&](int kt, auto steady_tag, auto start_tag, auto last_tag) {
             constexpr bool STEADY = decltype(steady_tag)::value, START = decltype(start_tag)::value;
+            constexpr bool LAST = decltype(last_tag)::value;      // a tile's last step: the next slab's fragments are not read
             constexpr bool START_OR_FIRST = START;
             const bool in1 = kt + 1 < nk, in2 = kt + 2 < nk;
             const bool more = STEADY || has_next || in1, more2 = STEADY || has_next || in2;
@@ -1289,7 +1293,7 @@ gemm_stream_kernel(GemmArgs g)
                     if (more2) wait_vm_lgkm<NA>(); else wait_vm_lgkm<0>();
                 }
                 __syncthreads();
-                read_a(a_next, 0, 0);
+                if constexpr (!LAST) read_a(a_next, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
             const uint8_t* sb_next = lds + (b_slot ^ 1) * B_SLOT + b_off;
@@ -1300,7 +1304,7 @@ gemm_stream_kernel(GemmArgs g)
                     const int q = s * TILES_N + j;
                     if (START_OR_FIRST && s == 0) mma(fa[(BLOCKS_M - 1) & 1][s], fb[s][j], acc[BLOCKS_M - 1][j], std::true_type{});
                     else mma(fa[(BLOCKS_M - 1) & 1][s], fb[s][j], acc[BLOCKS_M - 1][j], std::false_type{});
-                    if (more) fb[s][j] = read_frag(sb_next + j * R * kSlabBytes, s);
+                    if constexpr (!LAST) { if (more) fb[s][j] = read_frag(sb_next + j * R * kSlabBytes, s); }
 #pragma unroll
                     for (int c = 0; c < NB_TAIL; ++c)
                         if ((c * MMAS_PER_BLOCK) / NB_TAIL == q) {
@@ -1314,13 +1318,13 @@ gemm_stream_kernel(GemmArgs g)
             b_slot ^= 1;
         };
         using T = std::true_type; using F = std::false_type;
-        step(0, T{}, T{});
+        step(0, T{}, T{}, F{});
         // the next tile's coordinates: a few hundred scalar and vector instructions (divisions), here behind matrix
         // instructions already issued rather than between the epilogue and the first of them
         if (has_next) nxt = tile_of(t_next);
-        for (int kt = 1; kt < nk - 2; ++kt) step(kt, T{}, F{});
-        step(nk - 2, F{}, F{});
-        step(nk - 1, F{}, F{});
+        for (int kt = 1; kt < nk - 2; ++kt) step(kt, T{}, F{}, F{});
+        step(nk - 2, F{}, F{}, F{});
+        step(nk - 1, F{}, F{}, T{});
 
         if (has_next) {
             // what the next tile's first step would request before its barrier: the second half of its B slab 1 and
