@@ -46,7 +46,7 @@ def check_asm():
     instructions in front of an MFMA that uses it (wait states), (2) every LDS copy has its base address in scalar
     registers, (3) no MFMA goes through v_accvgpr_mov copies inside the loops (at most one initialisation pass), (4) the
     kernels on the throughput path use no scratch memory, (5) the streaming kernel initialises no accumulator by a
-    separate instruction and has no load the compiler knows of behind its first MFMA (with stores outstanding the
+    separate instruction and has no load the compiler knows of (outside the inline-assembly statements) behind its first MFMA (with stores outstanding the
     compiler waits for such a load with vmcnt(0), i.e. for every store).  Returns a list of findings (empty = clean)."""
     os.makedirs(OBJDIR, exist_ok=True)
     asm = os.path.join(OBJDIR, "qmm_gemm.s")
@@ -74,8 +74,14 @@ def check_asm():
             if not base.startswith("s["):
                 findings.append(f"{nm}: LDS copy with a vector base address ({off} {base})")
         if "gemm_stream_kernel" in nm:
-            first = next((k for k, l in enumerate(instrs) if l.startswith("v_mfma")), len(instrs))
-            late = [l for l in instrs[first:] if re.match(r"(global|flat|buffer|scratch)_load_(?!lds)", l)]
+            # instructions the compiler placed itself, i.e. outside the inline-assembly statements, behind the first MFMA
+            own, in_asm, seen_mfma = [], False, False
+            for l in (x.strip() for x in body.split("\n")):
+                if "#ASMSTART" in l: in_asm = True
+                elif "#ASMEND" in l: in_asm = False
+                elif l.startswith("v_mfma"): seen_mfma = True
+                elif seen_mfma and not in_asm and l and not l.startswith((";", ".")): own.append(l)
+            late = [l for l in own if re.match(r"(global|flat|buffer|scratch)_load_(?!lds)", l)]
             if late:
                 findings.append(f"{nm}: {len(late)} loads behind the first MFMA, e.g. '{late[0][:60]}'")
             if body.count("v_accvgpr_write") or body.count("v_accvgpr_mov"):

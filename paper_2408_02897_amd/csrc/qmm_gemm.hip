@@ -1212,12 +1212,14 @@ gemm_stream_kernel(GemmArgs g)
     for (int i = 0; i < NA; ++i) copy_a(cur.a + 2 * kSlabBytes, i, 2);
     wait_vm<NA + NB + NA>();
     __syncthreads();
-    // The two step sizes (one per operand: the host sends other granularities to gemm_kernel), fetched here and moved
+    // The two step sizes of the plain case (one per operand), fetched here and moved
     // to scalar registers at once: inside the loop there is then no load the compiler knows of, only stores -- with
     // both kinds outstanding it places full waits (vmcnt(0)) in front of the first use of a loaded register, and on
     // the way round the loop such a wait landed in the first step of every tile, behind all of the stores.
     const float delta_a = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, g.da[0])));
     const float delta_b = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, g.db[0])));
+    // any other granularity: the step sizes are fetched per tile, in the epilogue
+    const bool scales_in_loop = g.da_per_channel || g.db_per_channel || g.da_groups != 1 || g.db_groups != 1;
 
     int a_slot = 0, b_slot = 0;                // ring slots of the stream's current slab
     for (;;) {
@@ -1326,35 +1328,34 @@ gemm_stream_kernel(GemmArgs g)
         step(nk - 2, F{}, F{}, F{});
         step(nk - 1, F{}, F{}, T{});
 
-        if (has_next) {
-            // what the next tile's first step would request before its barrier: the second half of its B slab 1 and
-            // its A slab 2 (a_slot, b_slot now belong to its slab 0)
-            const int a_free = a_slot == 0 ? 2 : a_slot - 1;
+        // what the next tile's first step would request before its barrier: the second half of its B slab 1 and its
+        // A slab 2 (a_slot, b_slot now belong to its slab 0); then the wait states between the last matrix
+        // instruction and the first read of an accumulator
+        auto before_stores = [&]() {
+            if (has_next) {
+                const int a_free = a_slot == 0 ? 2 : a_slot - 1;
 #pragma unroll
-            for (int c = 0; c < NB - NB_TAIL; ++c) copy_b(nxt.b + kSlabBytes, NB_TAIL + c, b_slot ^ 1);
+                for (int c = 0; c < NB - NB_TAIL; ++c) copy_b(nxt.b + kSlabBytes, NB_TAIL + c, b_slot ^ 1);
 #pragma unroll
-            for (int i = 0; i < NA; ++i) copy_a(nxt.a + 2 * kSlabBytes, i, a_free);
-        }
-        // wait states between the last matrix instruction and the first read of an accumulator
-        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- epilogue of a whole tile: (acc * deltaA) * deltaB, in that order
-        {
-            const int64_t m_base = cur.m0 + wm * WM, n_base = cur.n0 + wn * WN;
-            int lane_e = lane;                    // kept out of the loop-invariant code the compiler would hoist
-            asm volatile("" : "+v"(lane_e));
-            const int64_t n = n_base + TILES_N * (lane_e & (R - 1));
-            const int lane_row = F8 ? 4 * (lane_e >> 4) : 4 * (lane_e >> 5);
-            auto row_in_block = [&](int r) -> int { return F8 ? lane_row + r : 8 * (r >> 2) + lane_row + (r & 3); };
-            auto value = [&](int ia, int r, int tt) -> float {
-                uint32_t raw;
-                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(raw) : "a"(acc[ia][tt][r]));
-                float a;
-                if constexpr (KIND == KIND_I8) a = (float)(int32_t)raw;
-                else a = __uint_as_float(raw);
-                return (a * delta_a) * delta_b;
-            };
+                for (int i = 0; i < NA; ++i) copy_a(nxt.a + 2 * kSlabBytes, i, a_free);
+            }
+            asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        const int64_t m_base = cur.m0 + wm * WM, n_base = cur.n0 + wn * WN;
+        int lane_e = lane;                    // kept out of the loop-invariant code the compiler would hoist
+        asm volatile("" : "+v"(lane_e));
+        const int64_t n = n_base + TILES_N * (lane_e & (R - 1));
+        const int lane_row = F8 ? 4 * (lane_e >> 4) : 4 * (lane_e >> 5);
+        auto row_in_block = [&](int r) -> int { return F8 ? lane_row + r : 8 * (r >> 2) + lane_row + (r & 3); };
+        auto accumulator = [&](int ia, int r, int tt) -> float {
+            uint32_t raw;
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(raw) : "a"(acc[ia][tt][r]));
+            if constexpr (KIND == KIND_I8) return (float)(int32_t)raw;
+            else return __uint_as_float(raw);
+        };
+        // the stores of a whole tile; value(ia, r, tt) = the descaled element of A block ia, register r, column tt
+        auto store_tile = [&](auto&& value) {
             if (g.y_bf16) {
                 uint8_t* ybase = static_cast<uint8_t*>(g.y) + ((cur.bidx * g.M + m_base) * g.N + n) * 2;
                 const int64_t row_bytes = g.N * 2;
@@ -1396,6 +1397,193 @@ gemm_stream_kernel(GemmArgs g)
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
+        };
+        // ---- epilogue of a whole tile: (acc * deltaA[row]) * deltaB[column], in that order
+        if (!scales_in_loop) {
+            before_stores();
+            store_tile([&](int ia, int r, int tt) -> float { return (accumulator(ia, r, tt) * delta_a) * delta_b; });
+        } else {
+            // Step sizes per channel or per batch group: fetched here, by loads the compiler does not see, waited for at
+            // once (one statement: the registers are valid when it ends) and in front of the copies for the next tile,
+            // so that the wait covers only copies requested a step ago.  About half a microsecond per tile, most of it
+            // behind the last block's matrix instructions still in the pipe.
+            auto finish = [&](auto a_tag, auto b_tag) {
+                constexpr bool A_PC = decltype(a_tag)::value, B_PC = decltype(b_tag)::value;
+                constexpr int NRA = F8 ? 8 : 16;                   // 16-byte loads of four consecutive rows' step sizes
+                typedef float f2v __attribute__((ext_vector_type(2)));
+                using ColT = typename std::conditional<F8, v4f, f2v>::type;
+                v4f ra[A_PC ? NRA : 1];
+                ColT cb;
+                float ra_s = 1.0f, cb_s = 1.0f;
+                const uint32_t ga = ((uint32_t)cur.bidx / (uint32_t)g.da_inner) % (uint32_t)g.da_groups;
+                const uint32_t gb = ((uint32_t)cur.bidx / (uint32_t)g.db_inner) % (uint32_t)g.db_groups;
+                const float* pa = g.da + (A_PC ? (int64_t)ga * g.M + m_base + lane_row : (int64_t)ga);
+                const float* pb = g.db + (B_PC ? (int64_t)gb * g.N + n : (int64_t)gb);
+#if defined(__HIP_DEVICE_COMPILE__)
+                if constexpr (F8 && !A_PC && !B_PC) {
+                    asm volatile("global_load_dword %[r0], %[pa], off\n\t"
+                        "global_load_dword %[c0], %[pb], off\n\t"
+                        "s_waitcnt vmcnt(0)"
+                        : [r0] "=&v"(ra_s),
+                          [c0] "=&v"(cb_s)
+                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
+                }
+                if constexpr (F8 && !A_PC && B_PC) {
+                    asm volatile("global_load_dword %[r0], %[pa], off\n\t"
+                        "global_load_dwordx4 %[c0], %[pb], off\n\t"
+                        "s_waitcnt vmcnt(0)"
+                        : [r0] "=&v"(ra_s),
+                          [c0] "=&v"(cb)
+                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
+                }
+                if constexpr (F8 && A_PC && !B_PC) {
+                    asm volatile("global_load_dwordx4 %[r0], %[pa], off\n\t"
+                        "global_load_dwordx4 %[r1], %[pa], off offset:64\n\t"
+                        "global_load_dwordx4 %[r2], %[pa], off offset:128\n\t"
+                        "global_load_dwordx4 %[r3], %[pa], off offset:192\n\t"
+                        "global_load_dwordx4 %[r4], %[pa], off offset:256\n\t"
+                        "global_load_dwordx4 %[r5], %[pa], off offset:320\n\t"
+                        "global_load_dwordx4 %[r6], %[pa], off offset:384\n\t"
+                        "global_load_dwordx4 %[r7], %[pa], off offset:448\n\t"
+                        "global_load_dword %[c0], %[pb], off\n\t"
+                        "s_waitcnt vmcnt(0)"
+                        : [r0] "=&v"(ra[0]),
+                          [r1] "=&v"(ra[1]),
+                          [r2] "=&v"(ra[2]),
+                          [r3] "=&v"(ra[3]),
+                          [r4] "=&v"(ra[4]),
+                          [r5] "=&v"(ra[5]),
+                          [r6] "=&v"(ra[6]),
+                          [r7] "=&v"(ra[7]),
+                          [c0] "=&v"(cb_s)
+                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
+                }
+                if constexpr (F8 && A_PC && B_PC) {
+                    asm volatile("global_load_dwordx4 %[r0], %[pa], off\n\t"
+                        "global_load_dwordx4 %[r1], %[pa], off offset:64\n\t"
+                        "global_load_dwordx4 %[r2], %[pa], off offset:128\n\t"
+                        "global_load_dwordx4 %[r3], %[pa], off offset:192\n\t"
+                        "global_load_dwordx4 %[r4], %[pa], off offset:256\n\t"
+                        "global_load_dwordx4 %[r5], %[pa], off offset:320\n\t"
+                        "global_load_dwordx4 %[r6], %[pa], off offset:384\n\t"
+                        "global_load_dwordx4 %[r7], %[pa], off offset:448\n\t"
+                        "global_load_dwordx4 %[c0], %[pb], off\n\t"
+                        "s_waitcnt vmcnt(0)"
+                        : [r0] "=&v"(ra[0]),
+                          [r1] "=&v"(ra[1]),
+                          [r2] "=&v"(ra[2]),
+                          [r3] "=&v"(ra[3]),
+                          [r4] "=&v"(ra[4]),
+                          [r5] "=&v"(ra[5]),
+                          [r6] "=&v"(ra[6]),
+                          [r7] "=&v"(ra[7]),
+                          [c0] "=&v"(cb)
+                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
+                }
+                if constexpr (!F8 && !A_PC && !B_PC) {
+                    asm volatile("global_load_dword %[r0], %[pa], off\n\t"
+                        "global_load_dword %[c0], %[pb], off\n\t"
+                        "s_waitcnt vmcnt(0)"
+                        : [r0] "=&v"(ra_s),
+                          [c0] "=&v"(cb_s)
+                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
+                }
+                if constexpr (!F8 && !A_PC && B_PC) {
+                    asm volatile("global_load_dword %[r0], %[pa], off\n\t"
+                        "global_load_dwordx2 %[c0], %[pb], off\n\t"
+                        "s_waitcnt vmcnt(0)"
+                        : [r0] "=&v"(ra_s),
+                          [c0] "=&v"(cb)
+                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
+                }
+                if constexpr (!F8 && A_PC && !B_PC) {
+                    asm volatile("global_load_dwordx4 %[r0], %[pa], off\n\t"
+                        "global_load_dwordx4 %[r1], %[pa], off offset:32\n\t"
+                        "global_load_dwordx4 %[r2], %[pa], off offset:64\n\t"
+                        "global_load_dwordx4 %[r3], %[pa], off offset:96\n\t"
+                        "global_load_dwordx4 %[r4], %[pa], off offset:128\n\t"
+                        "global_load_dwordx4 %[r5], %[pa], off offset:160\n\t"
+                        "global_load_dwordx4 %[r6], %[pa], off offset:192\n\t"
+                        "global_load_dwordx4 %[r7], %[pa], off offset:224\n\t"
+                        "global_load_dwordx4 %[r8], %[pa], off offset:256\n\t"
+                        "global_load_dwordx4 %[r9], %[pa], off offset:288\n\t"
+                        "global_load_dwordx4 %[r10], %[pa], off offset:320\n\t"
+                        "global_load_dwordx4 %[r11], %[pa], off offset:352\n\t"
+                        "global_load_dwordx4 %[r12], %[pa], off offset:384\n\t"
+                        "global_load_dwordx4 %[r13], %[pa], off offset:416\n\t"
+                        "global_load_dwordx4 %[r14], %[pa], off offset:448\n\t"
+                        "global_load_dwordx4 %[r15], %[pa], off offset:480\n\t"
+                        "global_load_dword %[c0], %[pb], off\n\t"
+                        "s_waitcnt vmcnt(0)"
+                        : [r0] "=&v"(ra[0]),
+                          [r1] "=&v"(ra[1]),
+                          [r2] "=&v"(ra[2]),
+                          [r3] "=&v"(ra[3]),
+                          [r4] "=&v"(ra[4]),
+                          [r5] "=&v"(ra[5]),
+                          [r6] "=&v"(ra[6]),
+                          [r7] "=&v"(ra[7]),
+                          [r8] "=&v"(ra[8]),
+                          [r9] "=&v"(ra[9]),
+                          [r10] "=&v"(ra[10]),
+                          [r11] "=&v"(ra[11]),
+                          [r12] "=&v"(ra[12]),
+                          [r13] "=&v"(ra[13]),
+                          [r14] "=&v"(ra[14]),
+                          [r15] "=&v"(ra[15]),
+                          [c0] "=&v"(cb_s)
+                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
+                }
+                if constexpr (!F8 && A_PC && B_PC) {
+                    asm volatile("global_load_dwordx4 %[r0], %[pa], off\n\t"
+                        "global_load_dwordx4 %[r1], %[pa], off offset:32\n\t"
+                        "global_load_dwordx4 %[r2], %[pa], off offset:64\n\t"
+                        "global_load_dwordx4 %[r3], %[pa], off offset:96\n\t"
+                        "global_load_dwordx4 %[r4], %[pa], off offset:128\n\t"
+                        "global_load_dwordx4 %[r5], %[pa], off offset:160\n\t"
+                        "global_load_dwordx4 %[r6], %[pa], off offset:192\n\t"
+                        "global_load_dwordx4 %[r7], %[pa], off offset:224\n\t"
+                        "global_load_dwordx4 %[r8], %[pa], off offset:256\n\t"
+                        "global_load_dwordx4 %[r9], %[pa], off offset:288\n\t"
+                        "global_load_dwordx4 %[r10], %[pa], off offset:320\n\t"
+                        "global_load_dwordx4 %[r11], %[pa], off offset:352\n\t"
+                        "global_load_dwordx4 %[r12], %[pa], off offset:384\n\t"
+                        "global_load_dwordx4 %[r13], %[pa], off offset:416\n\t"
+                        "global_load_dwordx4 %[r14], %[pa], off offset:448\n\t"
+                        "global_load_dwordx4 %[r15], %[pa], off offset:480\n\t"
+                        "global_load_dwordx2 %[c0], %[pb], off\n\t"
+                        "s_waitcnt vmcnt(0)"
+                        : [r0] "=&v"(ra[0]),
+                          [r1] "=&v"(ra[1]),
+                          [r2] "=&v"(ra[2]),
+                          [r3] "=&v"(ra[3]),
+                          [r4] "=&v"(ra[4]),
+                          [r5] "=&v"(ra[5]),
+                          [r6] "=&v"(ra[6]),
+                          [r7] "=&v"(ra[7]),
+                          [r8] "=&v"(ra[8]),
+                          [r9] "=&v"(ra[9]),
+                          [r10] "=&v"(ra[10]),
+                          [r11] "=&v"(ra[11]),
+                          [r12] "=&v"(ra[12]),
+                          [r13] "=&v"(ra[13]),
+                          [r14] "=&v"(ra[14]),
+                          [r15] "=&v"(ra[15]),
+                          [c0] "=&v"(cb)
+                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
+                }
+#endif
+                before_stores();
+                store_tile([&](int ia, int r, int tt) -> float {
+                    float sl, sr;
+                    if constexpr (A_PC) sl = F8 ? ra[ia][r] : ra[ia * 4 + (r >> 2)][r & 3]; else sl = ra_s;
+                    if constexpr (B_PC) sr = cb[tt]; else sr = cb_s;
+                    return (accumulator(ia, r, tt) * sl) * sr;
+                });
+            };
+            using T2 = std::true_type; using F2 = std::false_type;
+            if (g.da_per_channel) { if (g.db_per_channel) finish(T2{}, T2{}); else finish(T2{}, F2{}); }
+            else { if (g.db_per_channel) finish(F2{}, T2{}); else finish(F2{}, F2{}); }
         }
         if (!has_next) break;
         cur = nxt; t_cur = t_next;
@@ -1757,14 +1945,16 @@ qmm_status launch_shortk(GemmArgs& g, hipStream_t s)
     return launch_status();
 }
 
-// gemm_stream_kernel: codes in with one step size per operand, no split, whole 256 x 256 tiles, whole slabs and at
+// gemm_stream_kernel: codes in, no split, whole 256 x 256 tiles, whole slabs and at
 // least three of them, output in y alone, and more tiles than workgroups in the grid (with one tile each there is nothing to overlap).
 constexpr int kStreamGrid = 256;
 bool use_stream(const GemmArgs& g, int fuse)
 {
     if (fuse != 0 || g.splits > 1 || g.rowbytes % kSlabBytes != 0 || g.rowbytes < 3 * kSlabBytes) return false;
     if (g.M % 256 != 0 || g.N % 256 != 0 || !g.y || g.acc_out) return false;
-    if (g.da_per_channel || g.db_per_channel || g.da_groups != 1 || g.db_groups != 1) return false;   // one step size per operand
+    // (step sizes per channel are fetched four rows / columns at a time)
+    if (!aligned16(g.da) || !aligned16(g.db) || g.da_groups > 0x7FFFFFFF || g.db_groups > 0x7FFFFFFF ||
+        g.da_inner > 0x7FFFFFFF || g.db_inner > 0x7FFFFFFF) return false;
     return (g.M / 256) * (g.N / 256) * g.batch > kStreamGrid;
 }
 

@@ -283,17 +283,15 @@ def test_gemm_fp8_within_tolerance(shape, fa, fb):
 STREAM_SHAPES = [(1, 4352, 4352, 384), (3, 2560, 2560, 640), (1, 8192, 5120, 1024)]
 
 
-@pytest.mark.parametrize("shape", STREAM_SHAPES)
-@pytest.mark.parametrize("fa,fb", [(qmm.INT8, qmm.INT8), (qmm.E4M3, qmm.E4M3), (qmm.E5M2, qmm.E4M3), (qmm.E4M3, qmm.E5M2)])
-def test_gemm_streaming_kernel(shape, fa, fb):
-    """Accumulators (from the call that returns them) against the oracle on sampled rows of every matrix -- first and
-    last row, rows around tile borders -- then the y-only calls: every element equal to the oracle's descale of those
-    accumulators (binary32 and bfloat16 out)."""
+def _streaming_case(shape, fa, fb, a_pc, b_pc, a_groups, b_groups):
     bt, M, N, K = shape
     a = _random_codes(fa, (bt, M, K), 7); b = _random_codes(fb, (bt, N, K), 8)
     ta, tb = torch.from_numpy(a).to(DEV), torch.from_numpy(b).to(DEV)
-    da = np.array([3.7e-3], np.float32); db = np.array([9.1e-3], np.float32)
-    oa = qmm.operand(ta, fa, torch.from_numpy(da).to(DEV), False); ob = qmm.operand(tb, fb, torch.from_numpy(db).to(DEV), False)
+    rng = np.random.default_rng(M + N + a_groups)
+    da = rng.uniform(1e-3, 1e-2, a_groups * (M if a_pc else 1)).astype(np.float32)
+    db = rng.uniform(1e-3, 1e-2, b_groups * (N if b_pc else 1)).astype(np.float32)
+    oa = qmm.operand(ta, fa, torch.from_numpy(da).to(DEV), a_pc, a_groups)
+    ob = qmm.operand(tb, fb, torch.from_numpy(db).to(DEV), b_pc, b_groups)
     _, acc = qmm.gemm((ta, oa), (tb, ob), torch.float32, want_acc=True)
     acc = acc.cpu().numpy()
     rows = np.unique(np.concatenate([[0, 1, 255, 256, 257, M - 257, M - 256, M - 1],
@@ -307,10 +305,30 @@ def test_gemm_streaming_kernel(shape, fa, fb):
             bound = hw_fp8_bound(a[m:m + 1, rows], fa, b[m:m + 1], fb, sabs[None])[0]
             assert np.all(err <= bound), f"matrix {m}: err/bound {np.max(err / (bound + 1e-300)):.3f}"
     for out_dtype, out_bf16 in ((torch.float32, False), (torch.bfloat16, True)):
-        y = qmm.gemm((ta, oa), (tb, ob), out_dtype)
-        for m in range(bt):          # a matrix at a time: the oracle's descale works in binary64 copies
-            want_y = O.dequant(acc[m:m + 1].astype(np.float64), da, db, False, 1, False, 1, out_bf16)
-            assert np.array_equal(np32(y[m:m + 1]).view(np.uint32), want_y.view(np.uint32)), (m, out_dtype)
+        y = np32(qmm.gemm((ta, oa), (tb, ob), out_dtype))
+        want_y = O.dequant(acc.astype(np.float64), da, db, a_pc, a_groups, b_pc, b_groups, out_bf16)
+        assert np.array_equal(y.view(np.uint32), want_y.view(np.uint32)), out_dtype
+
+
+@pytest.mark.parametrize("shape", STREAM_SHAPES)
+@pytest.mark.parametrize("fa,fb", [(qmm.INT8, qmm.INT8), (qmm.E4M3, qmm.E4M3), (qmm.E5M2, qmm.E4M3), (qmm.E4M3, qmm.E5M2)])
+def test_gemm_streaming_kernel(shape, fa, fb):
+    """One step size per operand.  Accumulators (from the call that returns them) against the oracle on sampled rows
+    of every matrix -- first and last row, rows around tile borders -- then the y-only calls: every element equal to
+    the oracle's descale of those accumulators (binary32 and bfloat16 out)."""
+    _streaming_case(shape, fa, fb, False, False, 1, 1)
+
+
+@pytest.mark.parametrize("shape", STREAM_SHAPES)
+@pytest.mark.parametrize("fmt", [qmm.INT8, qmm.E4M3])
+@pytest.mark.parametrize("a_pc,b_pc,grouped", [(True, True, False), (True, False, False), (False, True, True), (False, False, True)])
+def test_gemm_streaming_kernel_step_sizes_per_channel_and_group(shape, fmt, a_pc, b_pc, grouped):
+    """The same kernel with step sizes per row of A and / or per column of B, and per batch group (the batched shape:
+    one group per matrix for A, one for the batch for B)."""
+    bt = shape[0]
+    if grouped and bt == 1:
+        pytest.skip("batch groups need a batch")
+    _streaming_case(shape, fmt, fmt, a_pc, b_pc, bt if grouped else 1, 1)
 
 
 def test_gemm_fp8_exact_cases():
