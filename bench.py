@@ -94,18 +94,25 @@ def main():
 
     for st in state:
         st["oa"] = qmm.operand(st["cx"], fmt, st["dx"]); st["ob"] = qmm.operand(st["cw"], fmt, st["dw"])
+        # activations and weights of a product go through scale and quantize together (qmm_scale_multi /
+        # qmm_quantize_multi: the tensor index is a grid dimension, so the 2-8 MB weight matrix, latency-bound on its
+        # own, rides in the activations' launches); argument arrays built once
+        st["xw"] = qmm.MultiDesc([st["x"], st["w"]])
+        st["d_ptrs"] = qmm.MultiDesc.pointers([st["dx"], st["dw"]])
+        st["c_ptrs"] = qmm.MultiDesc.pointers([st["cx"], st["cw"]])
 
     def step(record):
         for st in state:
-            timed("scale", record, lambda: (qmm.scale(st["x"], 1, fmt, out=st["dx"], workspace=st["ws"]),
-                                            qmm.scale(st["w"], 1, fmt, out=st["dw"], workspace=st["ws"])))
-            timed("quantize", record, lambda: (qmm.quantize(st["x"], 1, fmt, st["dx"], out=st["cx"]),
-                                               qmm.quantize(st["w"], 1, fmt, st["dw"], out=st["cw"])))
+            timed("scale", record, lambda: qmm.scale_multi(st["xw"], fmt, outs=[st["dx"], st["dw"]], workspace=st["ws"],
+                                                           out_ptrs=st["d_ptrs"]))
+            timed("quantize", record, lambda: qmm.quantize_multi(st["xw"], fmt, [st["dx"], st["dw"]],
+                                                                 outs=[st["cx"], st["cw"]], delta_ptrs=st["d_ptrs"],
+                                                                 out_ptrs=st["c_ptrs"]))
             timed("gemm", record, lambda: qmm.gemm((st["cx"], st["oa"]), (st["cw"], st["ob"]), out=st["y"]))
             timed("metric", record, lambda: qmm.metric(st["y"], st["y_ref"], out=st["m"], workspace=st["ws"]))
 
     # Timed region: K whole steps, with a pair of HIP events around every launch of the dominant kernel only (an
-    # event pair costs about 4 us of stream time; around all 36 launches of a step it would add a fifth to the step).
+    # event pair costs about 4 us of stream time; around all 24 launches of a step it would add a sixth to the step).
     for _ in range(args.warmup):
         step(())
     torch.cuda.synchronize()

@@ -126,6 +126,28 @@ qmm_status qmm_quantize(const qmm_tensor* x, qmm_format fmt, const qmm_granulari
                         const float* delta, qmm_round mode, uint64_t seed, uint64_t offset,
                         uint8_t* codes_out, void* stream);
 
+/*
+ * qmm_scale_multi / qmm_quantize_multi -- steps 1 and 2 (Eq. 1) for `count` tensors in one call each, e.g. the
+ * activations and the weights of one product: the results are those of `count` calls of qmm_scale / qmm_quantize.
+ *   x, g        host arrays of `count` descriptors / granularities.
+ *   delta_out, delta, codes_out   host arrays of `count` device pointers, each as the single-tensor call takes it.
+ *   offsets     host array of `count` stream offsets for stochastic rounding, or NULL for zeros.
+ *   workspace   device scratch, qmm_scale_multi_workspace_size() bytes (the tensors' own sizes, each rounded up to 16),
+ *               16-byte aligned.
+ * When all tensors (at most 8) are single dense bfloat16 matrices in 16-byte aligned whole vectors with one step size
+ * each (and, for quantize: contract_axis 1, cols a multiple of 16, round to nearest even), each call is one launch
+ * (two for scale: maxima, then one fold workgroup per tensor) with the tensor index as a grid dimension, so that the
+ * small tensors' latency-bound kernels run inside the large tensors' launches.  Otherwise the tensors are processed
+ * one after the other by the single-tensor code.  Errors as for the single-tensor calls; count = 0 is a no-op,
+ * count < 0 QMM_ERR_SHAPE.
+ */
+size_t qmm_scale_multi_workspace_size(int32_t count, const qmm_tensor* x, const qmm_granularity* g);
+qmm_status qmm_scale_multi(int32_t count, const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g,
+                           float* const* delta_out, void* workspace, size_t workspace_bytes, void* stream);
+qmm_status qmm_quantize_multi(int32_t count, const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g,
+                              const float* const* delta, qmm_round mode, uint64_t seed, const uint64_t* offsets,
+                              uint8_t* const* codes_out, void* stream);
+
 /* One operand of qmm_gemm: a dense batch [batch][rows][K] with K contiguous. */
 typedef struct {
     const void* data;        /* device; 8-bit codes, or bfloat16 values (see is_codes)          */

@@ -4,6 +4,7 @@
 // is x * (1/delta) with one IEEE reciprocal per thread-row and one product per
 // element.  Codes are written with the contracting axis contiguous; when the
 // input contracts over its rows the tile is transposed through LDS.
+#include <algorithm>
 #include "qmm_device.h"
 
 namespace qmm {
@@ -75,6 +76,27 @@ quantize_rows_bf16x16(QArgs a)
         }
     }
     *reinterpret_cast<u32x4*>(a.codes + p0) = out;
+}
+
+// Several dense bfloat16 tensors with one step size each, RTNE, rows contracting, in one launch
+// (qmm_quantize_multi): blockIdx.y picks the tensor; the arithmetic is quantize_rows_bf16x16's.
+constexpr int kMaxMulti = 8;
+struct MultiQ {
+    const uint16_t* x[kMaxMulti];
+    uint8_t* codes[kMaxMulti];
+    const float* delta[kMaxMulti];
+    int64_t nvec16[kMaxMulti];
+};
+template <int FMT> __global__ void __launch_bounds__(kThreads)
+quantize_flat_multi(MultiQ a)
+{
+    const int t = blockIdx.y;
+    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (v >= a.nvec16[t]) return;
+    const float rho = 1.0f / a.delta[t][0];
+    const u32x4* src = reinterpret_cast<const u32x4*>(a.x[t]) + 2 * v;
+    const u32x4 w0 = src[0], w1 = src[1];
+    reinterpret_cast<u32x4*>(a.codes[t])[v] = encode16_bf16_rtne<FMT>(w0, w1, rho);
 }
 
 // Generic path: one thread per output code, any dtype / stride / contracting axis.
@@ -269,4 +291,46 @@ extern "C" qmm_status qmm_quantize(const qmm_tensor* x, qmm_format fmt, const qm
     case QMM_FMT_E4M3: return launch_mode<QMM_FMT_E4M3>(x, a, mode, s);
     default: return launch_mode<QMM_FMT_E5M2>(x, a, mode, s);
     }
+}
+
+extern "C" qmm_status qmm_quantize_multi(int32_t count, const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g,
+                                         const float* const* delta, qmm_round mode, uint64_t seed, const uint64_t* offsets,
+                                         uint8_t* const* codes_out, void* stream)
+{
+    if (count < 0) return QMM_ERR_SHAPE;
+    if (count == 0) return QMM_OK;
+    if (!x || !g || !delta || !codes_out) return QMM_ERR_NULL;
+    if (fmt != QMM_FMT_INT8 && fmt != QMM_FMT_E4M3 && fmt != QMM_FMT_E5M2) return QMM_ERR_ENUM;
+    if (mode != QMM_ROUND_RTNE && mode != QMM_ROUND_STOCHASTIC) return QMM_ERR_ENUM;
+    bool one_launch = count <= kMaxMulti && mode == QMM_ROUND_RTNE;
+    for (int32_t t = 0; t < count && one_launch; ++t) {
+        const qmm_tensor& q = x[t];
+        one_launch = q.data && delta[t] && codes_out[t] && q.dtype == QMM_DT_BF16 && q.contract_axis == 1 && q.batch == 1 &&
+                     !g[t].per_channel && g[t].batch_groups == 1 && g[t].batch_inner >= 0 && q.rows >= 1 && q.cols >= 16 &&
+                     q.cols % 16 == 0 && q.row_stride == q.cols && aligned16(q.data) && aligned16(codes_out[t]);
+    }
+    if (!one_launch) {
+        for (int32_t t = 0; t < count; ++t) {
+            const qmm_status st = qmm_quantize(x + t, fmt, g + t, delta[t], mode, seed, offsets ? offsets[t] : 0, codes_out[t], stream);
+            if (st != QMM_OK) return st;
+        }
+        return QMM_OK;
+    }
+    MultiQ a{};
+    int64_t max_vec = 1;
+    for (int32_t t = 0; t < count; ++t) {
+        a.x[t] = static_cast<const uint16_t*>(x[t].data);
+        a.codes[t] = codes_out[t];
+        a.delta[t] = delta[t];
+        a.nvec16[t] = x[t].rows * x[t].cols / 16;
+        max_vec = std::max(max_vec, a.nvec16[t]);
+    }
+    const int64_t blocks = (max_vec + kThreads - 1) / kThreads;
+    if (blocks > 0x7FFFFFFF) return QMM_ERR_UNSUPPORTED;
+    hipStream_t s = as_stream(stream);
+    const dim3 grid((unsigned)blocks, (unsigned)count);
+    if (fmt == QMM_FMT_INT8) quantize_flat_multi<QMM_FMT_INT8><<<grid, kThreads, 0, s>>>(a);
+    else if (fmt == QMM_FMT_E4M3) quantize_flat_multi<QMM_FMT_E4M3><<<grid, kThreads, 0, s>>>(a);
+    else quantize_flat_multi<QMM_FMT_E5M2><<<grid, kThreads, 0, s>>>(a);
+    return launch_status();
 }

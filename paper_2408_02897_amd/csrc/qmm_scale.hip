@@ -5,6 +5,7 @@
 // maxima go to the workspace and a second small kernel folds them per group
 // and does the one division.  Two phases, no atomics, so the result does not
 // depend on launch geometry.
+#include <algorithm>
 #include "qmm_device.h"
 
 namespace qmm {
@@ -69,6 +70,60 @@ absmax_flat_bf16(const uint16_t* __restrict__ x, int64_t batch_stride, int64_t n
     }
     const uint32_t r = block_max_u32(finish_bf16(m));
     if (threadIdx.x == 0) partial[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = r;
+}
+
+// Several dense bfloat16 tensors, one step size each, in one launch (qmm_scale_multi): blockIdx.y picks the tensor,
+// workgroups past a tensor's own count leave at once.  The 2-8 MB weight matrices of a layer are latency-bound on
+// their own; launched beside the activations they cost next to nothing.
+constexpr int kMaxMulti = 8;
+struct MultiFlat {
+    const uint16_t* x[kMaxMulti];
+    int64_t nvec[kMaxMulti];        // 16-byte vectors
+    uint32_t* partial[kMaxMulti];
+    float* delta[kMaxMulti];
+    int nblk[kMaxMulti];
+};
+__global__ void __launch_bounds__(kThreads)
+absmax_flat_multi(MultiFlat a)
+{
+    const int t = blockIdx.y;
+    const int nblk = a.nblk[t];
+    if ((int)blockIdx.x >= nblk) return;
+    const u32x4* p = reinterpret_cast<const u32x4*>(a.x[t]);
+    const int64_t nvec = a.nvec[t];
+    u16x2 m[4] = {};
+    const int64_t stride = (int64_t)nblk * kThreads * 4;
+    int64_t i = (int64_t)blockIdx.x * kThreads * 4 + threadIdx.x;
+    for (; i + 3 * kThreads < nvec; i += stride) {
+        const u32x4 v0 = p[i], v1 = p[i + kThreads];
+        const u32x4 v2 = p[i + 2 * kThreads], v3 = p[i + 3 * kThreads];
+        fold_bf16x8(v0, m); fold_bf16x8(v1, m); fold_bf16x8(v2, m); fold_bf16x8(v3, m);
+    }
+    if (i < nvec) {
+        for (int u = 0; u < 4; ++u)
+            if (i + u * kThreads < nvec) fold_bf16x8(p[i + u * kThreads], m);
+    }
+    const uint32_t r = block_max_u32(finish_bf16(m));
+    if (threadIdx.x == 0) a.partial[t][blockIdx.x] = r;
+}
+// one workgroup per tensor: at most kMaxFlatBlocks partial maxima, all requested before folding
+__global__ void __launch_bounds__(kThreads)
+finalize_multi(MultiFlat a, float qmax)
+{
+    const int t = blockIdx.x;
+    const uint32_t* partial = a.partial[t];
+    const int nblk = a.nblk[t];
+    uint32_t v[kMaxFlatBlocks / kThreads];
+#pragma unroll
+    for (int k = 0; k < kMaxFlatBlocks / kThreads; ++k) {
+        const int b = threadIdx.x + k * kThreads;
+        v[k] = b < nblk ? partial[b] : 0u;
+    }
+    uint32_t m = 0;
+#pragma unroll
+    for (int k = 0; k < kMaxFlatBlocks / kThreads; ++k) m = max(m, v[k]);
+    m = block_max_u32(m);
+    if (threadIdx.x == 0) a.delta[t][0] = delta_from_absmax_bits(m, qmax);
 }
 
 template <typename T> QMM_DEV uint32_t mag_bits(T v);
@@ -402,5 +457,70 @@ extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_g
     else
         finalize_channels<<<dim3((unsigned)((C + 31) / 32), (unsigned)G), kThreads, 0, s>>>(
             partial, fold_batch, P, C, G, inner, qmax, delta_out);
+    return launch_status();
+}
+
+namespace {
+size_t multi_slice(const qmm_tensor* x, const qmm_granularity* g)
+{
+    return (qmm_scale_workspace_size(x, g) + 15u) & ~(size_t)15u;
+}
+// the tensors absmax_flat_multi takes: one matrix, dense, bfloat16 in whole 16-byte vectors, one step size
+bool multi_flat_ok(const qmm_tensor* x, const qmm_granularity* g)
+{
+    qmm_status st;
+    if (!valid_tensor(x, &st) || !x->data) return false;
+    return x->dtype == QMM_DT_BF16 && x->batch == 1 && !g->per_channel && g->batch_groups == 1 && g->batch_inner >= 0 &&
+           x->row_stride == x->cols && x->rows * x->cols >= 8 && (x->cols % 8 == 0) && aligned16(x->data) &&
+           make_plan(x, g).kind == Plan::FLAT;
+}
+}  // namespace
+
+extern "C" size_t qmm_scale_multi_workspace_size(int32_t count, const qmm_tensor* x, const qmm_granularity* g)
+{
+    if (count <= 0 || !x || !g) return 0;
+    size_t total = 0;
+    for (int32_t t = 0; t < count; ++t) total += multi_slice(x + t, g + t);
+    return total;
+}
+
+extern "C" qmm_status qmm_scale_multi(int32_t count, const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g,
+                                      float* const* delta_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (count < 0) return QMM_ERR_SHAPE;
+    if (count == 0) return QMM_OK;
+    if (!x || !g || !delta_out) return QMM_ERR_NULL;
+    if (fmt != QMM_FMT_INT8 && fmt != QMM_FMT_E4M3 && fmt != QMM_FMT_E5M2) return QMM_ERR_ENUM;
+    if (!workspace || workspace_bytes < qmm_scale_multi_workspace_size(count, x, g)) return QMM_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return QMM_ERR_ALIGN;
+    bool one_launch = count <= kMaxMulti;
+    for (int32_t t = 0; t < count && one_launch; ++t) one_launch = delta_out[t] && multi_flat_ok(x + t, g + t);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    if (!one_launch) {
+        for (int32_t t = 0; t < count; ++t) {
+            const size_t slice = multi_slice(x + t, g + t);
+            const qmm_status st = qmm_scale(x + t, fmt, g + t, delta_out[t], ws, slice, stream);
+            if (st != QMM_OK) return st;
+            ws += slice;
+        }
+        return QMM_OK;
+    }
+    MultiFlat a{};
+    int max_blk = 1;
+    for (int32_t t = 0; t < count; ++t) {
+        const Plan p = make_plan(x + t, g + t);          // FLAT for these tensors: the same workgroup count as qmm_scale
+        a.x[t] = static_cast<const uint16_t*>(x[t].data);
+        a.nvec[t] = x[t].rows * x[t].cols / 8;
+        a.partial[t] = reinterpret_cast<uint32_t*>(ws);
+        a.delta[t] = delta_out[t];
+        a.nblk[t] = p.flat_blocks;
+        max_blk = std::max(max_blk, p.flat_blocks);
+        ws += multi_slice(x + t, g + t);
+    }
+    const float qmax = fmt == QMM_FMT_INT8 ? 127.0f : (fmt == QMM_FMT_E4M3 ? 448.0f : 57344.0f);
+    hipStream_t s = as_stream(stream);
+    absmax_flat_multi<<<dim3((unsigned)max_blk, (unsigned)count), kThreads, 0, s>>>(a);
+    if (hipGetLastError() != hipSuccess) return QMM_ERR_LAUNCH;
+    finalize_multi<<<(unsigned)count, kThreads, 0, s>>>(a, qmax);
     return launch_status();
 }

@@ -13,7 +13,8 @@ INT8, E4M3, E5M2, BF16 = 0, 1, 2, 3
 DT_BF16, DT_F32 = 0, 1
 RTNE, STOCHASTIC = 0, 1
 FORMATS = {"int8": INT8, "e4m3": E4M3, "e5m2": E5M2, "bf16": BF16}
-EXPORTS = ["qmm_num_scales", "qmm_scale_workspace_size", "qmm_scale", "qmm_quantize", "qmm_gemm_workspace_size",
+EXPORTS = ["qmm_num_scales", "qmm_scale_workspace_size", "qmm_scale", "qmm_quantize", "qmm_scale_multi_workspace_size", "qmm_scale_multi", "qmm_quantize_multi",
+           "qmm_gemm_workspace_size",
            "qmm_gemm", "qmm_gemm_nsr_workspace_size", "qmm_gemm_nsr", "qmm_metric_workspace_size", "qmm_metric", "qmm_dequantize", "qmm_moments_workspace_size", "qmm_moments", "qmm_mfma_rate", "qmm_status_string", "qmm_version"]
 
 
@@ -55,6 +56,9 @@ def lib():
         L.qmm_scale_workspace_size.restype = sz; L.qmm_scale_workspace_size.argtypes = [TP, GP]
         L.qmm_scale.restype = i32; L.qmm_scale.argtypes = [TP, i32, GP, vp, vp, sz, vp]
         L.qmm_quantize.restype = i32; L.qmm_quantize.argtypes = [TP, i32, GP, vp, i32, u64, u64, vp, vp]
+        L.qmm_scale_multi_workspace_size.restype = sz; L.qmm_scale_multi_workspace_size.argtypes = [i32, vp, vp]
+        L.qmm_scale_multi.restype = i32; L.qmm_scale_multi.argtypes = [i32, vp, i32, vp, vp, vp, sz, vp]
+        L.qmm_quantize_multi.restype = i32; L.qmm_quantize_multi.argtypes = [i32, vp, i32, vp, vp, i32, u64, vp, vp, vp]
         L.qmm_gemm_workspace_size.restype = sz; L.qmm_gemm_workspace_size.argtypes = [OP, OP, i64, i64, i64, i64]
         L.qmm_gemm.restype = i32; L.qmm_gemm.argtypes = [OP, OP, i64, i64, i64, i64, vp, i32, vp, vp, sz, vp]
         L.qmm_gemm_nsr_workspace_size.restype = sz; L.qmm_gemm_nsr_workspace_size.argtypes = [i64, i64, i64]
@@ -139,6 +143,55 @@ def quantize(x, contract_axis, fmt, delta, per_channel=False, batch_groups=1, mo
     _check(L.qmm_quantize(ctypes.byref(t), fmt, ctypes.byref(g), delta.data_ptr(), mode, seed, offset,
                           out.data_ptr(), _stream()), "qmm_quantize")
     return out
+
+
+class MultiDesc:
+    """Host-side argument arrays of qmm_scale_multi / qmm_quantize_multi for a fixed list of tensors (built once,
+    reused: the arrays hold raw pointers, the object keeps their owners alive)."""
+    def __init__(self, xs, contract_axis=1, per_channel=False, batch_groups=1):
+        n = len(xs)
+        self.count = n
+        self.t = (Tensor * n)(*[tensor_desc(x, contract_axis) for x in xs])
+        self.g = (Granularity * n)(*[granularity(per_channel, batch_groups) for _ in xs])
+        self._keep = list(xs)
+        self.device = xs[0].device
+        self.shapes = [(d.batch, d.rows, d.cols) if contract_axis == 1 else (d.batch, d.cols, d.rows) for d in self.t]
+        self.num_scales = [lib().qmm_num_scales(ctypes.byref(self.t[i]), ctypes.byref(self.g[i])) for i in range(n)]
+
+    @staticmethod
+    def pointers(tensors):
+        arr = (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+        arr._keep = list(tensors)
+        return arr
+
+
+def scale_multi(desc, fmt, outs=None, workspace=None, out_ptrs=None):
+    """qmm_scale_multi on a MultiDesc: list of step-size tensors."""
+    L = lib()
+    if outs is None:
+        outs = [torch.empty(n, dtype=torch.float32, device=desc.device) for n in desc.num_scales]
+    if out_ptrs is None:
+        out_ptrs = MultiDesc.pointers(outs)
+    if workspace is None:
+        workspace = _workspace(L.qmm_scale_multi_workspace_size(desc.count, desc.t, desc.g), desc.device)
+    _check(L.qmm_scale_multi(desc.count, desc.t, fmt, desc.g, out_ptrs, workspace.data_ptr(), workspace.numel(), _stream()),
+           "qmm_scale_multi")
+    return outs
+
+
+def quantize_multi(desc, fmt, deltas, mode=RTNE, seed=0, offsets=None, outs=None, delta_ptrs=None, out_ptrs=None):
+    """qmm_quantize_multi on a MultiDesc: list of uint8 code tensors."""
+    L = lib()
+    if outs is None:
+        outs = [torch.empty(s, dtype=torch.uint8, device=desc.device) for s in desc.shapes]
+    if delta_ptrs is None:
+        delta_ptrs = MultiDesc.pointers(deltas)
+    if out_ptrs is None:
+        out_ptrs = MultiDesc.pointers(outs)
+    offs = (ctypes.c_uint64 * desc.count)(*offsets) if offsets is not None else None
+    _check(L.qmm_quantize_multi(desc.count, desc.t, fmt, desc.g, delta_ptrs, mode, seed, offs, out_ptrs, _stream()),
+           "qmm_quantize_multi")
+    return outs
 
 
 def operand(data, fmt, delta=None, per_channel=False, batch_groups=1, is_codes=True, batch_inner=1):

@@ -184,6 +184,42 @@ def test_scales_indexed_by_a_run_of_batch_dimensions(dims, groups, inner, per_ch
     assert np.array_equal(yb.float().cpu().numpy().view(np.uint32), want_yb.view(np.uint32))
 
 
+# ------------------------------------------------------------ several tensors per call
+@pytest.mark.parametrize("fmt", FMTS)
+def test_scale_and_quantize_multi_bit_exact(fmt):
+    """Activations and weights of a product in one call each (tensor index as a grid dimension): every step size and
+    code against the oracle; sizes from one vector to several workgroups' worth, a tensor of zeros among them."""
+    shapes = [(1, 2048, 1024), (1, 768, 768), (1, 1, 16), (1, 300, 4096), (1, 64, 64)]
+    xs = [W.student_t(sh, 4, seed=11 + i) for i, sh in enumerate(shapes)]
+    xs[4] = torch.zeros(shapes[4], dtype=torch.bfloat16)
+    xd = [x.to(DEV) for x in xs]
+    desc = qmm.MultiDesc(xd)
+    ds = qmm.scale_multi(desc, fmt)
+    cs = qmm.quantize_multi(desc, fmt, ds)
+    for x, d, c in zip(xs, ds, cs):
+        want_d = O.scale(np32(x), 1, fmt, False, 1)
+        assert np.array_equal(d.cpu().numpy().view(np.uint32), want_d.view(np.uint32))
+        assert np.array_equal(c.cpu().numpy(), O.quantize(np32(x), 1, fmt, want_d, False, 1))
+
+
+@pytest.mark.parametrize("case", ["per_channel", "transposed", "stochastic", "f32", "ragged_cols", "batched"])
+def test_scale_and_quantize_multi_other_cases_equal_single_calls(case):
+    """Tensors the one-launch kernels do not take go through the single-tensor code, one after the other."""
+    shape = (2, 96, 80) if case == "batched" else ((1, 96, 72) if case == "ragged_cols" else (1, 96, 80))
+    xs = [W.student_t(shape, 3, seed=21 + i).to(DEV) for i in range(3)]
+    if case == "f32": xs = [x.float() for x in xs]
+    ca = 0 if case == "transposed" else 1
+    pc = case == "per_channel"
+    mode, seed, offs = (qmm.STOCHASTIC, 5, [0, 8, 3]) if case == "stochastic" else (qmm.RTNE, 0, None)
+    desc = qmm.MultiDesc(xs, ca, pc)
+    ds = qmm.scale_multi(desc, qmm.E4M3)
+    cs = qmm.quantize_multi(desc, qmm.E4M3, ds, mode, seed, offs)
+    for i, x in enumerate(xs):
+        d0 = qmm.scale(x, ca, qmm.E4M3, pc)
+        c0 = qmm.quantize(x, ca, qmm.E4M3, d0, pc, 1, mode, seed, offs[i] if offs else 0)
+        assert torch.equal(d0, ds[i]) and torch.equal(c0, cs[i])
+
+
 # ------------------------------------------------------------------------- gemm
 def _random_codes(fmt, shape, seed):
     g = torch.Generator(); g.manual_seed(seed)
