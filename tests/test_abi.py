@@ -115,3 +115,28 @@ def test_gemm_nsr_argument_errors(L):
     assert call(codes, codes, fake, fake, fake, None, 0) == 6               # no workspace
     assert call(codes, codes, fake, fake, fake, fake, need - 1) == 6        # workspace too small
     assert call(codes, codes, fake, ctypes.c_void_p(0x1004), fake, fake, need) == 4   # misaligned reference
+
+
+def test_multi_tensor_argument_errors(L):
+    """qmm_scale_multi / qmm_quantize_multi report argument errors before any launch (no GPU needed)."""
+    n = 2
+    ts = (qmm.Tensor * n)(qmm.Tensor(None, qmm.DT_BF16, 1, 1, 4, 16, 64, 16), qmm.Tensor(None, qmm.DT_BF16, 1, 1, 8, 32, 256, 32))
+    gs = (qmm.Granularity * n)(qmm.granularity(False, 1), qmm.granularity(False, 1))
+    fake = ctypes.c_void_p(0x1000)
+    ptrs = (ctypes.c_void_p * n)(0x1000, 0x2000)
+    need = L.qmm_scale_multi_workspace_size(n, ts, gs)
+    assert need >= 32 and need % 16 == 0
+    assert L.qmm_scale_multi_workspace_size(0, ts, gs) == 0
+    assert L.qmm_scale_multi(0, ts, qmm.E4M3, gs, ptrs, None, 0, None) == 0            # nothing to do
+    assert L.qmm_scale_multi(-1, ts, qmm.E4M3, gs, ptrs, fake, 1024, None) == 2
+    assert L.qmm_scale_multi(n, None, qmm.E4M3, gs, ptrs, fake, 1024, None) == 1
+    assert L.qmm_scale_multi(n, ts, 9, gs, ptrs, fake, 1024, None) == 3
+    assert L.qmm_scale_multi(n, ts, qmm.E4M3, gs, ptrs, fake, need - 1, None) == 6
+    assert L.qmm_scale_multi(n, ts, qmm.E4M3, gs, ptrs, ctypes.c_void_p(0x1004), 1024, None) == 4
+    assert L.qmm_quantize_multi(0, ts, qmm.E4M3, gs, ptrs, qmm.RTNE, 0, None, ptrs, None) == 0
+    assert L.qmm_quantize_multi(-1, ts, qmm.E4M3, gs, ptrs, qmm.RTNE, 0, None, ptrs, None) == 2
+    assert L.qmm_quantize_multi(n, ts, qmm.E4M3, gs, None, qmm.RTNE, 0, None, ptrs, None) == 1
+    assert L.qmm_quantize_multi(n, ts, 9, gs, ptrs, qmm.RTNE, 0, None, ptrs, None) == 3
+    assert L.qmm_quantize_multi(n, ts, qmm.E4M3, gs, ptrs, 5, 0, None, ptrs, None) == 3
+    # tensors with NULL data go to the single-tensor code, which reports them
+    assert L.qmm_quantize_multi(n, ts, qmm.E4M3, gs, ptrs, qmm.RTNE, 0, None, ptrs, None) == 1
