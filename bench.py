@@ -287,11 +287,12 @@ def main():
             ms = sorted(ts)[len(ts) // 2]
             return {"bytes_per_launch": nbytes, "ms_per_launch": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
                     "frac_hbm": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        return {"what": "largest X of the step (scale, quantize) and largest Y (metric), 10 launches back to back per "
+        return {"what": "largest X of the step (scale, quantize, moments) and largest Y (metric), 10 launches back to back per "
                         "event pair, operands rotated over 3 copies",
                 "scale": rate(2 * nx, lambda k: qmm.scale(xs[k], 1, fmt, out=dx, workspace=ws)),
                 "quantize": rate(3 * nx, lambda k: qmm.quantize(xs[k], 1, fmt, dx, out=cs[k])),
-                "metric": rate(6 * ny, lambda k: qmm.metric(big_y["y"], big_y["y_ref"], out=m, workspace=ws))}
+                "metric": rate(6 * ny, lambda k: qmm.metric(big_y["y"], big_y["y_ref"], out=m, workspace=ws)),
+                "moments": rate(2 * nx, lambda k: qmm.moments(xs[k], out=mom, workspace=ws))}
     passes["largest_tensors"] = passes_on_largest()
 
     # ---- the oracle timed on the host cores, on a bounded sample of the same workload
