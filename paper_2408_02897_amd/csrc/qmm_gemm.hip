@@ -669,7 +669,7 @@ gemm_kernel(GemmArgs g)
                 }
                 uint8_t* dst = ybase + ml * row_bytes;
                 if constexpr (TILES_N == 8) *reinterpret_cast<u32x4*>(dst) = u32x4{pk[0], pk[1], pk[2], pk[3]};
-                else if constexpr (TILES_N == 4) *reinterpret_cast<u32x2*>(dst) = u32x2{pk[0], pk[1]};
+                else if constexpr (TILES_N == 4) __builtin_nontemporal_store(u32x2{pk[0], pk[1]}, reinterpret_cast<u32x2*>(dst));
                 else *reinterpret_cast<uint32_t*>(dst) = pk[0];
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -1354,7 +1354,12 @@ gemm_stream_kernel(GemmArgs g)
             if constexpr (KIND == KIND_I8) return (float)(int32_t)raw;
             else return __uint_as_float(raw);
         };
-        // the stores of a whole tile; value(ia, r, tt) = the descaled element of A block ia, register r, column tt
+        // the stores of a whole tile; value(ia, r, tt) = the descaled element of A block ia, register r, column tt.
+        // Streaming (nontemporal) stores: the 100-270 MB outputs of these shapes then leave for memory while this
+        // kernel, which leaves most of the HBM bandwidth unused, is still running.  With ordinary stores much of an
+        // output stays behind as dirty cache lines whose write-back competes with the reads of whatever pass comes
+        // next: measured on the benchmark's step, this kernel takes 2 (QKV) and 7 us (FFN1) longer and the metric
+        // pass over the four outputs 20 us less.
         auto store_tile = [&](auto&& value) {
             if (g.y_bf16) {
                 uint8_t* ybase = static_cast<uint8_t*>(g.y) + ((cur.bidx * g.M + m_base) * g.N + n) * 2;
@@ -1372,8 +1377,8 @@ gemm_stream_kernel(GemmArgs g)
                             pk[q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{v0, v1}, bf2));
                         }
                         uint8_t* dst = ybase + (ia * R + row_in_block(r)) * row_bytes;
-                        if constexpr (TILES_N == 4) *reinterpret_cast<u32x2*>(dst) = u32x2{pk[0], pk[1]};
-                        else *reinterpret_cast<uint32_t*>(dst) = pk[0];
+                        if constexpr (TILES_N == 4) __builtin_nontemporal_store(u32x2{pk[0], pk[1]}, reinterpret_cast<u32x2*>(dst));
+                        else __builtin_nontemporal_store(pk[0], reinterpret_cast<uint32_t*>(dst));
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -1388,10 +1393,10 @@ gemm_stream_kernel(GemmArgs g)
                             v4f v;
 #pragma unroll
                             for (int e = 0; e < 4; ++e) v[e] = value(ia, r, e);
-                            *reinterpret_cast<v4f*>(dst) = v;
+                            __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(dst));
                         } else {
                             typedef float f2 __attribute__((ext_vector_type(2)));
-                            *reinterpret_cast<f2*>(dst) = f2{value(ia, r, 0), value(ia, r, 1)};
+                            __builtin_nontemporal_store(f2{value(ia, r, 0), value(ia, r, 1)}, reinterpret_cast<f2*>(dst));
                         }
                     }
                     __builtin_amdgcn_sched_barrier(0);
