@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 # HBM bytes per GEMM launch (mean of the four launches of a step) from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
 # very command, scaled by what the same counters read for a plain 256 MiB copy (factors 2.00 and 1.00); the summary
 # with the commands is profiles/bench_bert_large_fwd_e4m3.md.  Other workloads / formats: not collected (null).
-GEMM_TRAFFIC = {("bert_large_fwd", "e4m3"): {"read_bytes": 72.6e6, "write_bytes": 75.5e6,
+GEMM_TRAFFIC = {("bert_large_fwd", "e4m3"): {"read_bytes": 56.6e6, "write_bytes": 75.6e6,
                                              "algorithmic_read_bytes": 32.4e6, "algorithmic_write_bytes": 75.4e6}}
 PEAK = {"e4m3": 5000.0, "e5m2": 5000.0, "int8": 5000.0}   # dense MFMA TFLOP/s (TOP/s), MI355X
 HBM_PEAK_GBS = 8000.0
