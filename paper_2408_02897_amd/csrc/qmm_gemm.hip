@@ -1014,8 +1014,8 @@ gemm_shortk_kernel(GemmArgs g)
                         uint32_t pk[TILES_N / 2];
                         packed_row(ia, r, pk);
                         uint8_t* dst = ybase + (ia * R + row_in_block(r)) * row_bytes;
-                        if constexpr (TILES_N == 4) *reinterpret_cast<u32x2*>(dst) = u32x2{pk[0], pk[1]};
-                        else *reinterpret_cast<uint32_t*>(dst) = pk[0];
+                        if constexpr (TILES_N == 4) __builtin_nontemporal_store(u32x2{pk[0], pk[1]}, reinterpret_cast<u32x2*>(dst));
+                        else __builtin_nontemporal_store(pk[0], reinterpret_cast<uint32_t*>(dst));
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -1028,7 +1028,7 @@ gemm_shortk_kernel(GemmArgs g)
                         v4f v;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) v[e] = value(ia, r, e);
-                        *reinterpret_cast<v4f*>(ybase + (int64_t)(ia * R + row_in_block(r)) * g.N) = v;
+                        __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(ybase + (int64_t)(ia * R + row_in_block(r)) * g.N));
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
