@@ -133,7 +133,7 @@ template <> QMM_DEV uint32_t mag_bits<float>(float v) { return __float_as_uint(v
 // One wavefront per (matrix, row): partial[b*rows + r] = absmax of the row.  Any stride, any dtype.
 template <typename T> __global__ void __launch_bounds__(kThreads)
 absmax_rows(const T* __restrict__ x, int64_t batch_stride, int64_t row_stride, int64_t rows, int64_t cols,
-            int64_t total_rows, uint32_t* __restrict__ partial)
+            int64_t total_rows, uint32_t* __restrict__ partial, float qmax, float* __restrict__ delta)
 {
     const int64_t wr = (int64_t)blockIdx.x * (kThreads / kWave) + threadIdx.x / kWave;
     if (wr >= total_rows) return;
@@ -154,14 +154,16 @@ absmax_rows(const T* __restrict__ x, int64_t batch_stride, int64_t row_stride, i
         for (int64_t i = lane; i < cols; i += kWave) m = max(m, mag_bits<T>(p[i]));
     }
     m = wave_max_u32(m);
-    if (lane == 0) partial[wr] = m;
+    // delta != NULL: every row is a scale group of its own (one step size per row, one matrix per batch group), so
+    // the row's maximum is final and the step size is written here, without the second kernel
+    if (lane == 0) { if (delta) delta[wr] = delta_from_absmax_bits(m, qmax); else partial[wr] = m; }
 }
 
 // Short rows (at most 256 bfloat16 columns, 16-byte aligned rows): LPR lanes per row, one 16-byte vector each, so a
 // wavefront takes 64 / LPR rows at once instead of one (with the rows dense in memory it reads 1 KB contiguous).
 template <int LPR> __global__ void __launch_bounds__(kThreads)
 absmax_rows_short(const uint16_t* __restrict__ x, int64_t batch_stride, int64_t row_stride, int64_t rows, int64_t cols,
-                  int64_t total_rows, uint32_t* __restrict__ partial)
+                  int64_t total_rows, uint32_t* __restrict__ partial, float qmax, float* __restrict__ delta)
 {
     constexpr int RPW = kWave / LPR;
     const int lane = threadIdx.x & (kWave - 1);
@@ -177,7 +179,7 @@ absmax_rows_short(const uint16_t* __restrict__ x, int64_t batch_stride, int64_t 
     }
 #pragma unroll
     for (int off = LPR / 2; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off, kWave));
-    if (v == 0 && row < total_rows) partial[row] = m;
+    if (v == 0 && row < total_rows) { if (delta) delta[row] = delta_from_absmax_bits(m, qmax); else partial[row] = m; }
 }
 
 // Column groups: workgroup = 32 column-vectors (256 columns) x 8 row lanes over a slab of rows.
@@ -404,6 +406,9 @@ extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_g
     const int64_t C = p.C;
     int64_t P = p.P;
 
+    // one step size per row with every matrix a batch group of its own: a row's maximum is its group's maximum
+    const bool rows_are_groups = nelem > 0 && p.kind == Plan::ROWS && g->per_channel && x->contract_axis == 1 && p.P == 1 &&
+                                 x->batch == g->batch_groups && g->batch_inner <= 1;
     if (nelem > 0) {
         switch (p.kind) {
         case Plan::FLAT:
@@ -412,6 +417,7 @@ extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_g
             break;
         case Plan::ROWS: {
             const int64_t total = x->batch * x->rows;
+            float* direct = rows_are_groups ? delta_out : nullptr;
             const unsigned nb = (unsigned)((total + kThreads / kWave - 1) / (kThreads / kWave));
             if (p.vec && x->cols <= 256) {
                 const uint16_t* xp = static_cast<const uint16_t*>(x->data);
@@ -419,16 +425,16 @@ extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_g
                 const int lpr = nvec <= 1 ? 1 : nvec <= 2 ? 2 : nvec <= 4 ? 4 : nvec <= 8 ? 8 : nvec <= 16 ? 16 : 32;
                 const int64_t waves = (total + kWave / lpr - 1) / (kWave / lpr);
                 const unsigned nbs = (unsigned)((waves + kThreads / kWave - 1) / (kThreads / kWave));
-#define QMM_ROWS_SHORT(L) absmax_rows_short<L><<<nbs, kThreads, 0, s>>>(xp, x->batch_stride, x->row_stride, x->rows, x->cols, total, partial)
+#define QMM_ROWS_SHORT(L) absmax_rows_short<L><<<nbs, kThreads, 0, s>>>(xp, x->batch_stride, x->row_stride, x->rows, x->cols, total, partial, qmax, direct)
                 if (lpr == 1) QMM_ROWS_SHORT(1); else if (lpr == 2) QMM_ROWS_SHORT(2); else if (lpr == 4) QMM_ROWS_SHORT(4);
                 else if (lpr == 8) QMM_ROWS_SHORT(8); else if (lpr == 16) QMM_ROWS_SHORT(16); else QMM_ROWS_SHORT(32);
 #undef QMM_ROWS_SHORT
             } else if (bf16)
                 absmax_rows<uint16_t><<<nb, kThreads, 0, s>>>(static_cast<const uint16_t*>(x->data), x->batch_stride,
-                                                               x->row_stride, x->rows, x->cols, total, partial);
+                                                               x->row_stride, x->rows, x->cols, total, partial, qmax, direct);
             else
                 absmax_rows<float><<<nb, kThreads, 0, s>>>(static_cast<const float*>(x->data), x->batch_stride,
-                                                            x->row_stride, x->rows, x->cols, total, partial);
+                                                            x->row_stride, x->rows, x->cols, total, partial, qmax, direct);
             break;
         }
         case Plan::COLS_VEC:
@@ -447,6 +453,7 @@ extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_g
         }
         }
         if (hipGetLastError() != hipSuccess) return QMM_ERR_LAUNCH;
+        if (rows_are_groups) return launch_status();
     }
     // An empty tensor has no partials: fold over zero matrices so every group gets delta = 1.
     const int64_t fold_batch = nelem > 0 ? x->batch : 0;
