@@ -97,7 +97,7 @@ int64_t qmm_num_scales(const qmm_tensor* x, const qmm_granularity* g);
  * Defined results: the maximum is taken over magnitude bit patterns, so an
  * inf or NaN element makes its group's delta inf / NaN; an all-zero (or
  * empty) group gets delta = 1; a quotient below 2^-126 is raised to 2^-126.
- * fmt must be one of the three 8-bit formats.
+ * fmt must be one of the three 8-bit formats.  batch above 65535: QMM_ERR_UNSUPPORTED.
  */
 size_t qmm_scale_workspace_size(const qmm_tensor* x, const qmm_granularity* g);
 qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g,
@@ -120,7 +120,7 @@ qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_granularity*
  *   codes_out  device, [batch][non-contracting][contracting] bytes, dense: the
  *              contracting axis is contiguous whatever contract_axis is.
  *   delta      device, as written by qmm_scale (or supplied by the caller).
- * Uses no workspace.
+ * Uses no workspace.  batch above 65535: QMM_ERR_UNSUPPORTED.
  */
 qmm_status qmm_quantize(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g,
                         const float* delta, qmm_round mode, uint64_t seed, uint64_t offset,
@@ -138,8 +138,9 @@ qmm_status qmm_quantize(const qmm_tensor* x, qmm_format fmt, const qmm_granulari
  * each (and, for quantize: contract_axis 1, cols a multiple of 16, round to nearest even), each call is one launch
  * (two for scale: maxima, then one fold workgroup per tensor) with the tensor index as a grid dimension, so that the
  * small tensors' latency-bound kernels run inside the large tensors' launches.  Otherwise the tensors are processed
- * one after the other by the single-tensor code.  Errors as for the single-tensor calls; count = 0 is a no-op,
- * count < 0 QMM_ERR_SHAPE.
+ * one after the other by the single-tensor code, after every tensor's arguments have been checked (an argument
+ * error in any of them is returned before anything is launched).  Errors as for the single-tensor calls; count = 0
+ * is a no-op, count < 0 QMM_ERR_SHAPE.
  */
 size_t qmm_scale_multi_workspace_size(int32_t count, const qmm_tensor* x, const qmm_granularity* g);
 qmm_status qmm_scale_multi(int32_t count, const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g,

@@ -37,6 +37,7 @@
 //    several whole tiles per CU and one step size per operand: gemm_stream_kernel
 //    (both: workgroups that stay on their CU and overlap a tile's stores with the
 //    next tile's work).
+#include <atomic>
 #include <type_traits>
 
 #include <cstdlib>
@@ -1869,6 +1870,20 @@ int plan_splits(int64_t M, int64_t N, int64_t rowbytes, int64_t batch, int fuse)
     return splits >= 2 ? (int)splits : 1;
 }
 
+// The dynamic-LDS limit of a kernel is a property of the function on one device: it is applied once per
+// (instantiation, device), the devices already served kept as a bit mask (devices past 63 are served on every call).
+// Two host threads that meet here both apply it, which is harmless; nothing else is remembered between calls.
+static inline bool ensure_lds_attr(std::atomic<uint64_t>& done, const void* kern, int bytes)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    const uint64_t bit = dev < 64 ? (1ull << dev) : 0;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return true;
+    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return false;
+    if (bit) done.fetch_or(bit, std::memory_order_release);
+    return true;
+}
+
 template <int KIND, int FA, int FB, int TM, int TG, int NWN, int FUSE, int NSR = 0>
 qmm_status launch_tile(GemmArgs& g, hipStream_t s)
 {
@@ -1879,12 +1894,8 @@ qmm_status launch_tile(GemmArgs& g, hipStream_t s)
     const int64_t total = (int64_t)g.tiles_m * g.tiles_n * g.batch * g.splits;
     if (total > 0x7FFFFFFF) return QMM_ERR_UNSUPPORTED;
     auto kern = gemm_kernel<KIND, FA, FB, TM, TG, NWN, FUSE, NSR>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
-            return QMM_ERR_LAUNCH;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_attr_done{0};
+    if (!ensure_lds_attr(lds_attr_done, reinterpret_cast<const void*>(kern), LDS_BYTES)) return QMM_ERR_LAUNCH;
     kern<<<(unsigned)total, 64 * kWavesM * NWN, LDS_BYTES, s>>>(g);
     if constexpr (NSR != 0) {
         if (hipGetLastError() != hipSuccess) return QMM_ERR_LAUNCH;
@@ -1940,12 +1951,8 @@ qmm_status launch_shortk(GemmArgs& g, hipStream_t s)
     g.tiles_n = (int)(g.N / 256);
     if ((int64_t)g.tiles_m * g.tiles_n * g.batch > 0x7FFFFFFF) return QMM_ERR_UNSUPPORTED;
     auto kern = gemm_shortk_kernel<KIND, FA, FB>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
-            return QMM_ERR_LAUNCH;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_attr_done{0};
+    if (!ensure_lds_attr(lds_attr_done, reinterpret_cast<const void*>(kern), LDS_BYTES)) return QMM_ERR_LAUNCH;
     kern<<<kShortKGrid, 512, LDS_BYTES, s>>>(g);
     return launch_status();
 }
@@ -1971,12 +1978,8 @@ qmm_status launch_stream(GemmArgs& g, hipStream_t s)
     g.tiles_n = (int)(g.N / 256);
     if ((int64_t)g.tiles_m * g.tiles_n * g.batch > 0x7FFFFFFF) return QMM_ERR_UNSUPPORTED;
     auto kern = gemm_stream_kernel<KIND, FA, FB>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
-            return QMM_ERR_LAUNCH;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_attr_done{0};
+    if (!ensure_lds_attr(lds_attr_done, reinterpret_cast<const void*>(kern), LDS_BYTES)) return QMM_ERR_LAUNCH;
     kern<<<kStreamGrid, 512, LDS_BYTES, s>>>(g);
     return launch_status();
 }

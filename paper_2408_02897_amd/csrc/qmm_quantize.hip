@@ -262,8 +262,10 @@ template <int FMT> qmm_status launch_mode(const qmm_tensor* x, const QArgs& a, q
 
 using namespace qmm;
 
-extern "C" qmm_status qmm_quantize(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g, const float* delta,
-                                   qmm_round mode, uint64_t seed, uint64_t offset, uint8_t* codes_out, void* stream)
+namespace {
+// Everything qmm_quantize can refuse, checked without launching: QMM_OK means the call will enqueue (or has nothing to do).
+qmm_status quantize_check(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g, const float* delta,
+                          qmm_round mode, const uint8_t* codes_out)
 {
     if (!x || !g) return QMM_ERR_NULL;
     if (x->dtype != QMM_DT_BF16 && x->dtype != QMM_DT_F32) return QMM_ERR_ENUM;
@@ -276,6 +278,16 @@ extern "C" qmm_status qmm_quantize(const qmm_tensor* x, qmm_format fmt, const qm
     if (x->batch > 65535) return QMM_ERR_UNSUPPORTED;
     if (x->batch * x->rows * x->cols == 0) return QMM_OK;
     if (!x->data || !delta || !codes_out) return QMM_ERR_NULL;
+    return QMM_OK;
+}
+}  // namespace
+
+extern "C" qmm_status qmm_quantize(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g, const float* delta,
+                                   qmm_round mode, uint64_t seed, uint64_t offset, uint8_t* codes_out, void* stream)
+{
+    const qmm_status chk = quantize_check(x, fmt, g, delta, mode, codes_out);
+    if (chk != QMM_OK) return chk;
+    if (x->batch * x->rows * x->cols == 0) return QMM_OK;
 
     QArgs a;
     a.x = x->data; a.delta = delta; a.codes = codes_out;
@@ -310,6 +322,10 @@ extern "C" qmm_status qmm_quantize_multi(int32_t count, const qmm_tensor* x, qmm
                      q.cols % 16 == 0 && q.row_stride == q.cols && aligned16(q.data) && aligned16(codes_out[t]);
     }
     if (!one_launch) {
+        for (int32_t t = 0; t < count; ++t) {      // every tensor's arguments before the first launch
+            const qmm_status st = quantize_check(x + t, fmt, g + t, delta[t], mode, codes_out[t]);
+            if (st != QMM_OK) return st;
+        }
         for (int32_t t = 0; t < count; ++t) {
             const qmm_status st = qmm_quantize(x + t, fmt, g + t, delta[t], mode, seed, offsets ? offsets[t] : 0, codes_out[t], stream);
             if (st != QMM_OK) return st;

@@ -382,20 +382,31 @@ extern "C" size_t qmm_scale_workspace_size(const qmm_tensor* x, const qmm_granul
     return (size_t)(words > 0 ? words : 1) * sizeof(uint32_t);
 }
 
-extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g, float* delta_out,
-                                void* workspace, size_t workspace_bytes, void* stream)
+namespace {
+// Everything qmm_scale can refuse, checked without launching.
+qmm_status scale_check(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g, const float* delta_out,
+                       const void* workspace, size_t workspace_bytes)
 {
     qmm_status st;
     if (!g || !delta_out) return QMM_ERR_NULL;
     if (!valid_tensor(x, &st)) return st;
     if (fmt != QMM_FMT_INT8 && fmt != QMM_FMT_E4M3 && fmt != QMM_FMT_E5M2) return QMM_ERR_ENUM;
     if (g->batch_groups < 1 || g->batch_inner < 0 || (g->per_channel != 0 && g->per_channel != 1)) return QMM_ERR_ENUM;
-    const int64_t nscales = qmm_num_scales(x, g);
-    if (nscales == 0) return QMM_OK;
+    if (x->batch > 65535) return QMM_ERR_UNSUPPORTED;          // the batch index is a grid dimension in some plans
+    if (qmm_num_scales(x, g) == 0) return QMM_OK;
     if (x->batch * x->rows * x->cols > 0 && !x->data) return QMM_ERR_NULL;
-    const size_t need = qmm_scale_workspace_size(x, g);
-    if (!workspace || workspace_bytes < need) return QMM_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < qmm_scale_workspace_size(x, g)) return QMM_ERR_WORKSPACE;
     if (!aligned16(workspace)) return QMM_ERR_ALIGN;
+    return QMM_OK;
+}
+}  // namespace
+
+extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g, float* delta_out,
+                                void* workspace, size_t workspace_bytes, void* stream)
+{
+    const qmm_status chk = scale_check(x, fmt, g, delta_out, workspace, workspace_bytes);
+    if (chk != QMM_OK) return chk;
+    if (qmm_num_scales(x, g) == 0) return QMM_OK;
 
     hipStream_t s = as_stream(stream);
     uint32_t* partial = static_cast<uint32_t*>(workspace);
@@ -504,6 +515,13 @@ extern "C" qmm_status qmm_scale_multi(int32_t count, const qmm_tensor* x, qmm_fo
     for (int32_t t = 0; t < count && one_launch; ++t) one_launch = delta_out[t] && multi_flat_ok(x + t, g + t);
     uint8_t* ws = static_cast<uint8_t*>(workspace);
     if (!one_launch) {
+        uint8_t* probe = ws;
+        for (int32_t t = 0; t < count; ++t) {      // every tensor's arguments before the first launch
+            const size_t slice = multi_slice(x + t, g + t);
+            const qmm_status st = scale_check(x + t, fmt, g + t, delta_out[t], probe, slice);
+            if (st != QMM_OK) return st;
+            probe += slice;
+        }
         for (int32_t t = 0; t < count; ++t) {
             const size_t slice = multi_slice(x + t, g + t);
             const qmm_status st = qmm_scale(x + t, fmt, g + t, delta_out[t], ws, slice, stream);

@@ -30,17 +30,24 @@ def backward_error_sweep(dofs=W.BACKWARD_ERROR_DOFS, formats=(qmm.INT8, qmm.E4M3
     return [backward_error_row(d, f, n, device) for d in dofs for f in formats]
 
 
-def relative_error_profile(fmt, points=4096, decades=11.0, device="cuda:0"):
-    """Relative error of Eq. 2 over magnitudes (the figure comparing the three formats under RTNE): `points`
-    positive bfloat16 magnitudes log-spaced over `decades` decades below the largest one, 1.0, which the step size
-    maps onto the format's largest code.  Returns (magnitudes, relative errors) as float32 CPU tensors; a value
-    quantized to zero has relative error 1."""
-    x = torch.logspace(-decades, 0.0, points, dtype=torch.float32).to(torch.bfloat16).to(device).reshape(1, -1)
+def relative_error_profile(fmt, points_per_decade=384, decades=11, device="cuda:0"):
+    """Relative error of Eq. 2 over magnitudes (the figure comparing the three formats under RTNE): positive bfloat16
+    magnitudes log-spaced over `decades` decades below the largest one, 1.0, which the step size maps onto the
+    format's largest code.  Library calls only: scale -> quantize -> dequantize, then qmm_metric over each decade's
+    slice, whose Eq. 2 fields are the profile.  Returns one dict per decade d (magnitudes in (10^-(d+1), 10^-d]):
+    re_max, re_mean (a value quantized to zero has relative error 1) and the number of magnitudes."""
+    n = points_per_decade * decades
+    x = torch.logspace(-float(decades), 0.0, n + 1, dtype=torch.float32)[1:].to(torch.bfloat16).to(device).reshape(1, -1)
     delta = qmm.scale(x, 1, fmt)
     codes = qmm.quantize(x, 1, fmt, delta)
-    v = qmm.dequantize(codes, fmt, delta)
-    xf = x.float()
-    return xf.reshape(-1).cpu(), ((v.reshape(1, -1) - xf).abs() / xf).reshape(-1).cpu()
+    v = qmm.dequantize(codes, fmt, delta).reshape(-1)
+    xf = x.float().reshape(-1)
+    rows = []
+    for d in range(decades):
+        lo, hi = n - (d + 1) * points_per_decade, n - d * points_per_decade
+        f = dict(zip(qmm.METRIC_FIELDS, qmm.metric(v[lo:hi].contiguous(), xf[lo:hi].contiguous()).cpu().tolist()))
+        rows.append({"decade": d, "re_max": f["RE_max"], "re_mean": f["RE_sum"] / max(f["RE_cnt"], 1.0), "n": int(f["RE_cnt"])})
+    return rows
 
 
 # Candidates of the per-op choice, cheapest scaling first: one step size per tensor before one per channel.  The
@@ -93,10 +100,8 @@ def main():
     print("\nworst relative error of a value (Eq. 2) per decade of magnitude below the tensor's largest one")
     print(f"{'decade':>10s} " + " ".join(f"{n:>10s}" for n in ("int8", "e4m3", "e5m2")))
     prof = {f: relative_error_profile(f) for f in (qmm.INT8, qmm.E4M3, qmm.E5M2)}
-    x = prof[qmm.INT8][0]
     for d in range(0, 11):
-        sel = (x <= 10.0 ** -d) & (x > 10.0 ** -(d + 1))
-        print(f"  1e-{d + 1:<2d}..1e-{d:<2d}" + " ".join(f"{float(prof[f][1][sel].max()):10.3e}" for f in (qmm.INT8, qmm.E4M3, qmm.E5M2)))
+        print(f"  1e-{d + 1:<2d}..1e-{d:<2d}" + " ".join(f"{prof[f][d]['re_max']:10.3e}" for f in (qmm.INT8, qmm.E4M3, qmm.E5M2)))
     print("\nnoise-to-signal ratio per op, BERT-large forward shapes (synthetic operands), format x granularity;"
           " choice = first candidate with NSR <= 1e-3")
     print(f"{'op':>9s} " + " ".join(f"{names[f] + ('/ch' if pc else '/t'):>10s}" for f, pc in CANDIDATES) + "  choice")

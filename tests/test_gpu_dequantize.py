@@ -48,20 +48,31 @@ def test_roundtrip_of_quantize(fmt, shape, per_channel, groups):
 
 
 def test_relative_error_profile_matches_oracle_and_closed_forms():
+    """Per decade of magnitude below the tensor's largest value: worst and mean relative error of Eq. 2 from the
+    library (scale -> quantize -> dequantize -> metric per slice) against the oracle's chain on the same magnitudes,
+    and the closed forms: at most 2^-(M+1) for FP8 values in the normal range, at most delta / (2 x) for INT8."""
+    ppd, decades = 384, 11
+    n = ppd * decades
+    x = torch.logspace(-float(decades), 0.0, n + 1, dtype=torch.float32)[1:].to(torch.bfloat16).float().numpy()
     for fmt, worst_normal in ((qmm.INT8, None), (qmm.E4M3, 2.0 ** -4), (qmm.E5M2, 2.0 ** -3)):
-        x, re = experiments.relative_error_profile(fmt)
-        xo = x.numpy().reshape(1, -1)
+        rows = experiments.relative_error_profile(fmt, ppd, decades)
+        xo = x.reshape(1, -1)
         do = O.scale(xo, 1, fmt)
         vo = O.dequantize_codes(O.quantize(xo, 1, fmt, do), fmt, do)
-        want = np.abs(vo - xo) / xo
-        assert np.allclose(re.numpy(), want.reshape(-1), rtol=1e-6, atol=0)
-        if worst_normal is not None:
-            qmax = 448.0 if fmt == qmm.E4M3 else 57344.0
-            minnorm = (2.0 ** -6 if fmt == qmm.E4M3 else 2.0 ** -14) / qmax
-            sel = x.numpy() > 1.01 * minnorm
-            assert re.numpy()[sel].max() <= worst_normal * (1 + 1e-6)
-        else:
-            assert np.all(re.numpy() <= 1.0 / (254.0 * x.numpy()) * (1 + 1e-3) + 1e-7)
+        re = (np.abs(vo.astype(np.float64) - xo) / xo).reshape(-1)
+        qmax = 448.0 if fmt == qmm.E4M3 else 57344.0
+        for r in rows:
+            d = r["decade"]
+            sl = re[n - (d + 1) * ppd: n - d * ppd]
+            assert r["n"] == ppd
+            assert r["re_max"] == sl.max(), (fmt, d)
+            assert abs(r["re_mean"] - sl.mean()) <= 1e-12 * sl.mean()
+            if worst_normal is not None:
+                minnorm = (2.0 ** -6 if fmt == qmm.E4M3 else 2.0 ** -14) / qmax
+                if 10.0 ** -(d + 1) > 1.01 * minnorm:
+                    assert r["re_max"] <= worst_normal * (1 + 1e-6)
+            else:
+                assert r["re_max"] <= min(1.0, 1.0 / (254.0 * 10.0 ** -(d + 1)) * (1 + 1e-3) + 1e-7)
 
 
 def test_empty_and_odd_sizes():
