@@ -57,7 +57,8 @@ typedef enum {
     QMM_ERR_ALIGN = 4,       /* pointer or extent alignment rule violated         */
     QMM_ERR_UNSUPPORTED = 5, /* valid request this build does not implement       */
     QMM_ERR_WORKSPACE = 6,   /* workspace missing or too small                    */
-    QMM_ERR_LAUNCH = 7       /* the HIP runtime refused a launch                  */
+    QMM_ERR_LAUNCH = 7,      /* the HIP runtime refused a launch                  */
+    QMM_ERR_LIMIT = 8        /* input larger than a fixed, documented capacity    */
 } qmm_status;
 
 /* 8-bit formats of the paper, plus the un-quantized pass-through used for the
@@ -102,6 +103,23 @@ int64_t qmm_num_scales(const qmm_tensor* x, const qmm_granularity* g);
 size_t qmm_scale_workspace_size(const qmm_tensor* x, const qmm_granularity* g);
 qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g,
                      float* delta_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * qmm_scale_static -- qmm_scale for callers that cannot allocate device memory or hand over a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same arguments, results and errors as
+ * qmm_scale without the workspace: the partial maxima go to a scratch array of QMM_SCALE_STATIC_BYTES that is part
+ * of the library's device image (one copy per GPU, held until the process ends; its address is looked up once per
+ * device on the first call there).  The call allocates and frees nothing.
+ *   Limit: qmm_scale_workspace_size(x, g) must not exceed QMM_SCALE_STATIC_BYTES, else QMM_ERR_LIMIT (checked on
+ *   the host before anything is launched; 1 MiB covers one step size per tensor for any size, and e.g. one step
+ *   size per row for 262144 rows).
+ *   Nothing in the array has to be cleared between calls (every word read by the second kernel has been written by
+ *   the first of the same call), but all calls on one GPU share it: calls that may overlap on one GPU -- different
+ *   streams, or graphs replayed concurrently -- race on it and must be serialised by the caller.
+ */
+#define QMM_SCALE_STATIC_BYTES (1u << 20)
+qmm_status qmm_scale_static(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g,
+                            float* delta_out, void* stream);
 
 /*
  * Step 2 -- quantize (Eq. 1: code = round(X / delta)).  The quotient is formed

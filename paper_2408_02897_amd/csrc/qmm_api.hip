@@ -12,6 +12,7 @@ extern "C" const char* qmm_status_string(qmm_status s)
     case QMM_ERR_UNSUPPORTED: return "not supported by this build";
     case QMM_ERR_WORKSPACE: return "workspace missing or too small";
     case QMM_ERR_LAUNCH: return "kernel launch failed";
+    case QMM_ERR_LIMIT: return "input exceeds a fixed capacity of the call";
     }
     return "unknown status";
 }

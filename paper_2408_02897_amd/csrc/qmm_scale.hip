@@ -6,6 +6,7 @@
 // and does the one division.  Two phases, no atomics, so the result does not
 // depend on launch geometry.
 #include <algorithm>
+#include <atomic>
 #include "qmm_device.h"
 
 namespace qmm {
@@ -476,6 +477,42 @@ extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_g
         finalize_channels<<<dim3((unsigned)((C + 31) / 32), (unsigned)G), kThreads, 0, s>>>(
             partial, fold_batch, P, C, G, inner, qmax, delta_out);
     return launch_status();
+}
+
+// ---- qmm_scale_static: the same kernels with their partial maxima in a scratch array of the device image.
+// `scratch` below is the host-side stand-in of the device array; its device address differs per GPU and is looked
+// up once per device (kept in scratch_addr), and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[QMM_SCALE_STATIC_BYTES];
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> scratch_addr[kMaxDevices];
+
+qmm_status static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return QMM_ERR_LAUNCH;
+    if (dev < 0 || dev >= kMaxDevices) return QMM_ERR_UNSUPPORTED;
+    void* p = scratch_addr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return QMM_ERR_LAUNCH;
+        scratch_addr[dev].store(p, std::memory_order_release);      // two first callers store the same address
+    }
+    *out = p;
+    return QMM_OK;
+}
+}  // namespace
+
+extern "C" qmm_status qmm_scale_static(const qmm_tensor* x, qmm_format fmt, const qmm_granularity* g, float* delta_out,
+                                       void* stream)
+{
+    // argument errors first, exactly as qmm_scale reports them (the workspace checks cannot fail with a dummy of full size)
+    const qmm_status chk = scale_check(x, fmt, g, delta_out, reinterpret_cast<const void*>(uintptr_t(256)), ~size_t(0));
+    if (chk != QMM_OK) return chk;
+    if (qmm_scale_workspace_size(x, g) > QMM_SCALE_STATIC_BYTES) return QMM_ERR_LIMIT;
+    void* ws = nullptr;
+    const qmm_status st = static_scratch(&ws);
+    if (st != QMM_OK) return st;
+    return qmm_scale(x, fmt, g, delta_out, ws, QMM_SCALE_STATIC_BYTES, stream);
 }
 
 namespace {

@@ -13,7 +13,7 @@ INT8, E4M3, E5M2, BF16 = 0, 1, 2, 3
 DT_BF16, DT_F32 = 0, 1
 RTNE, STOCHASTIC = 0, 1
 FORMATS = {"int8": INT8, "e4m3": E4M3, "e5m2": E5M2, "bf16": BF16}
-EXPORTS = ["qmm_num_scales", "qmm_scale_workspace_size", "qmm_scale", "qmm_quantize", "qmm_scale_multi_workspace_size", "qmm_scale_multi", "qmm_quantize_multi",
+EXPORTS = ["qmm_num_scales", "qmm_scale_workspace_size", "qmm_scale", "qmm_scale_static", "qmm_quantize", "qmm_scale_multi_workspace_size", "qmm_scale_multi", "qmm_quantize_multi",
            "qmm_gemm_workspace_size",
            "qmm_gemm", "qmm_gemm_nsr_workspace_size", "qmm_gemm_nsr", "qmm_metric_workspace_size", "qmm_metric", "qmm_dequantize", "qmm_moments_workspace_size", "qmm_moments", "qmm_mfma_rate", "qmm_status_string", "qmm_version"]
 
@@ -55,6 +55,7 @@ def lib():
         L.qmm_num_scales.restype = i64; L.qmm_num_scales.argtypes = [TP, GP]
         L.qmm_scale_workspace_size.restype = sz; L.qmm_scale_workspace_size.argtypes = [TP, GP]
         L.qmm_scale.restype = i32; L.qmm_scale.argtypes = [TP, i32, GP, vp, vp, sz, vp]
+        L.qmm_scale_static.restype = i32; L.qmm_scale_static.argtypes = [TP, i32, GP, vp, vp]
         L.qmm_quantize.restype = i32; L.qmm_quantize.argtypes = [TP, i32, GP, vp, i32, u64, u64, vp, vp]
         L.qmm_scale_multi_workspace_size.restype = sz; L.qmm_scale_multi_workspace_size.argtypes = [i32, vp, vp]
         L.qmm_scale_multi.restype = i32; L.qmm_scale_multi.argtypes = [i32, vp, i32, vp, vp, vp, sz, vp]
@@ -128,6 +129,17 @@ def scale(x, contract_axis, fmt, per_channel=False, batch_groups=1, out=None, wo
         workspace = _workspace(need, x.device)
     _check(L.qmm_scale(ctypes.byref(t), fmt, ctypes.byref(g), out.data_ptr(), workspace.data_ptr(),
                        workspace.numel(), _stream()), "qmm_scale")
+    return out
+
+
+def scale_static(x, contract_axis, fmt, per_channel=False, batch_groups=1, out=None, batch_inner=1):
+    """qmm_scale_static: qmm_scale with the library's own scratch array (no workspace, nothing allocated by the call
+    itself when `out` is given)."""
+    L = lib()
+    t, g = tensor_desc(x, contract_axis), granularity(per_channel, batch_groups, batch_inner)
+    if out is None:
+        out = torch.empty(L.qmm_num_scales(ctypes.byref(t), ctypes.byref(g)), dtype=torch.float32, device=x.device)
+    _check(L.qmm_scale_static(ctypes.byref(t), fmt, ctypes.byref(g), out.data_ptr(), _stream()), "qmm_scale_static")
     return out
 
 

@@ -57,6 +57,12 @@ def test_argument_errors_are_reported_before_any_launch(L):
     t4 = qmm.Tensor(fake, qmm.DT_BF16, 1, 1, 4, 16, 64, 16)
     assert L.qmm_scale(ctypes.byref(t4), qmm.E4M3, ctypes.byref(g), fake, None, 0, None) == 6
     assert L.qmm_quantize(ctypes.byref(t4), qmm.E4M3, ctypes.byref(g), fake, 5, 0, 0, fake, None) == 3
+    # the entry point with the library's own scratch: same argument errors, and its size limit, all on the host
+    assert L.qmm_scale_static(ctypes.byref(t), qmm.E4M3, ctypes.byref(g), None, None) == 1
+    assert L.qmm_scale_static(ctypes.byref(t), 7, ctypes.byref(g), fake, None) == 3
+    assert L.qmm_scale_static(ctypes.byref(t3), qmm.E4M3, ctypes.byref(g), fake, None) == 2
+    wide = qmm.Tensor(fake, qmm.DT_BF16, 0, 8, 8, 40960, 8 * 40960, 40960)      # per-column maxima of 8 matrices: > 1 MiB of partials
+    assert L.qmm_scale_static(ctypes.byref(wide), qmm.E4M3, ctypes.byref(qmm.granularity(True, 1)), fake, None) == 8
     bad = qmm.granularity(False, 1, -1)                       # negative run length of the scale groups
     assert L.qmm_scale(ctypes.byref(t4), qmm.E4M3, ctypes.byref(bad), fake, fake, 1024, None) == 3
     assert L.qmm_quantize(ctypes.byref(t4), qmm.E4M3, ctypes.byref(bad), fake, 0, 0, 0, fake, None) == 3
