@@ -3,14 +3,21 @@
 
 One "step" = one pass of the whole path over the forward GEMMs of one BERT-large encoder layer
 (16384 tokens, hidden 1024, FFN 4096: QKV, attention output, FFN1, FFN2): for every op
-    qmm_scale(X), qmm_scale(W), qmm_quantize(X), qmm_quantize(W), qmm_gemm (+descale, bf16 out), qmm_metric(Y, Y_ref)
-with E4M3 operands, per-tensor step sizes, synthetic seeded inputs already resident in HBM.  The
-high-precision reference product Y_ref is an input of the metric pass and is computed once, outside
-the timed region (it is the un-quantized baseline the method compares against, not part of the
-quantized path).  Prints ONE JSON line.
+    qmm_scale(X, W), qmm_quantize(X, W), qmm_gemm (+descale, bf16 out), qmm_metric(Y, Y_ref)
+with per-tensor step sizes, synthetic seeded inputs already resident in HBM.  The high-precision reference product
+Y_ref is an input of the metric pass and is computed once, outside the timed region (it is the un-quantized baseline
+the method compares against, not part of the quantized path).  The headline (`value`, `roofline`, `passes`) is that
+step in E4M3; the same line carries, measured after the timed region:
+    int8        the same step in INT8 (the metric names both types)
+    ops         every product of the layer -- forward, dgrad, wgrad; E4M3 (gradients E5M2) and INT8; step sizes per
+                tensor and per channel -- as GEMM time, TFLOP/s and fraction of the 5.0 PFLOP/s peak
+    attention   the batched products of BERT-large attention (32 x 16 heads, 512 x 512 x 64), bound by their output
+                stream: GB/s of codes in + Y out
+    ceilings    what plain streaming kernels reach on buffers larger than the caches (read, copy)
+Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_large_fwd|bert_base_fwd]
-                    [--format e4m3|e5m2|int8] [--no-cpu-baseline]
+                    [--format e4m3|e5m2|int8] [--no-cpu-baseline] [--no-extras]
 """
 import argparse
 import json
@@ -22,13 +29,20 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per GEMM launch (mean of the four launches of a step) from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
-# very command, scaled by what the same counters read for a plain 256 MiB copy (factors 2.00 and 1.00); the summary
-# with the commands is profiles/bench_bert_large_fwd_e4m3.md.  Other workloads / formats: not collected (null).
-GEMM_TRAFFIC = {("bert_large_fwd", "e4m3"): {"read_bytes": 56.6e6, "write_bytes": 75.6e6,
-                                             "algorithmic_read_bytes": 32.4e6, "algorithmic_write_bytes": 75.4e6}}
+# HBM bytes per GEMM launch by format, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this very command: written by
+# `python -m paper_2408_02897_amd.traffic` from the counter files (the commands are in profiles/).
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemm_traffic.json")
 PEAK = {"e4m3": 5000.0, "e5m2": 5000.0, "int8": 5000.0}   # dense MFMA TFLOP/s (TOP/s), MI355X
 HBM_PEAK_GBS = 8000.0
+DTYPE = {"e4m3": "fp8_e4m3", "e5m2": "fp8_e5m2", "int8": "int8"}
+
+
+def load_traffic(workload, fmt_name):
+    try:
+        with open(TRAFFIC_FILE) as f:
+            return json.load(f).get(f"{workload}/{fmt_name}")
+    except (OSError, ValueError):
+        return None
 
 
 def main():
@@ -39,6 +53,7 @@ def main():
     ap.add_argument("--workload", default="bert_large_fwd", choices=["bert_large_fwd", "bert_base_fwd"])
     ap.add_argument("--format", default="e4m3", choices=["e4m3", "e5m2", "int8"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="only the timed step (what the profiling commands run)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten plain device copies of 256 MiB (to scale the FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
@@ -60,9 +75,26 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read_per_copy": n, "bytes_written_per_copy": n, "copies": 10}}))
         return
-    fmt = qmm.FORMATS[args.format]
     cfg_no, dims = (4, W.BERT_LARGE) if args.workload == "bert_large_fwd" else (2, W.BERT_BASE)
     ops = W.bert_forward_ops(**dims)
+    flops = sum(op.flops for op in ops)
+
+    def event_pair():
+        return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def back_to_back_ms(fn, launches=10, repeats=4):
+        """median over repeats - 1 of (time of `launches` calls between one event pair) / launches"""
+        ts = []
+        for it in range(repeats):
+            e0, e1 = event_pair()
+            e0.record()
+            for k in range(launches):
+                fn(k)
+            e1.record()
+            torch.cuda.synchronize()
+            if it >= 1:
+                ts.append(e0.elapsed_time(e1) / launches)
+        return sorted(ts)[len(ts) // 2]
 
     # ---- inputs, resident in HBM; reference products (untimed)
     state = []
@@ -78,82 +110,109 @@ def main():
         st["m"] = torch.empty(16, dtype=torch.float64, device=dev)
         st["ws"] = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
         st["host_x"], st["host_w"] = x, w
-        state.append(st)
-    torch.cuda.synchronize()
-
-    kinds = ("scale", "quantize", "gemm", "metric")
-    events = {k: [] for k in kinds}
-
-    def timed(kind, record, fn):
-        if kind in record:
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(); fn(); e1.record()
-            events[kind].append((e0, e1))
-        else:
-            fn()
-
-    for st in state:
-        st["oa"] = qmm.operand(st["cx"], fmt, st["dx"]); st["ob"] = qmm.operand(st["cw"], fmt, st["dw"])
         # activations and weights of a product go through scale and quantize together (qmm_scale_multi /
         # qmm_quantize_multi: the tensor index is a grid dimension, so the 2-8 MB weight matrix, latency-bound on its
         # own, rides in the activations' launches); argument arrays built once
         st["xw"] = qmm.MultiDesc([st["x"], st["w"]])
         st["d_ptrs"] = qmm.MultiDesc.pointers([st["dx"], st["dw"]])
         st["c_ptrs"] = qmm.MultiDesc.pointers([st["cx"], st["cw"]])
-
-    def step(record):
-        for st in state:
-            timed("scale", record, lambda: qmm.scale_multi(st["xw"], fmt, outs=[st["dx"], st["dw"]], workspace=st["ws"],
-                                                           out_ptrs=st["d_ptrs"]))
-            timed("quantize", record, lambda: qmm.quantize_multi(st["xw"], fmt, [st["dx"], st["dw"]],
-                                                                 outs=[st["cx"], st["cw"]], delta_ptrs=st["d_ptrs"],
-                                                                 out_ptrs=st["c_ptrs"]))
-            timed("gemm", record, lambda: qmm.gemm((st["cx"], st["oa"]), (st["cw"], st["ob"]), out=st["y"]))
-            timed("metric", record, lambda: qmm.metric(st["y"], st["y_ref"], out=st["m"], workspace=st["ws"]))
-
-    # Timed region: K whole steps, with a pair of HIP events around every launch of the dominant kernel only (an
-    # event pair costs about 4 us of stream time; around all 24 launches of a step it would add a sixth to the step).
-    for _ in range(args.warmup):
-        step(())
+        state.append(st)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(("gemm",))
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    # The other kernel classes are timed the same way in K further steps, outside the timed region.
-    for _ in range(args.steps):
-        step(("scale", "quantize", "metric"))
-    torch.cuda.synchronize()
-    # The tensor-moments pass (not a step of the quantized product: it characterises the operands beforehand) over
-    # the same X and W, timed the same way.
-    events["moments"] = []
-    mom = torch.empty(8, dtype=torch.float64, device=dev)
-    for _ in range(args.steps):
-        for st in state:
-            timed("moments", ("moments",), lambda: (qmm.moments(st["x"], out=mom, workspace=st["ws"]),
-                                                    qmm.moments(st["w"], out=mom, workspace=st["ws"])))
-    torch.cuda.synchronize()
-
-    flops = sum(op.flops for op in ops)
-    ms_per_step = dt / args.steps * 1e3
-    value = flops / (dt / args.steps) / 1e12
-
-    # ---- per-kernel-class device time from HIP events on the launch stream
-    per_kind_ms = {k: sum(a.elapsed_time(b) for a, b in v) / args.steps for k, v in events.items()}
     elems_x = sum(op.M * op.K for op in ops); elems_w = sum(op.N * op.K for op in ops); elems_y = sum(op.M * op.N for op in ops)
     algo_bytes = {"scale": 2 * (elems_x + elems_w), "quantize": 3 * (elems_x + elems_w),
                   "metric": (2 + 4) * elems_y, "moments": 2 * (elems_x + elems_w)}
-    gemm_ms_per_launch = per_kind_ms["gemm"] / len(ops)
-    gemm_tflops = flops / (per_kind_ms["gemm"] * 1e-3) / 1e12
+
+    def run_steps(fmt_name, steps, warmup):
+        """The step in one format: wall clock around `steps` steps with an event pair around every GEMM launch, then
+        `steps` further steps with event pairs around the other kernel classes."""
+        fmt = qmm.FORMATS[fmt_name]
+        kinds = ("scale", "quantize", "gemm", "metric")
+        events = {k: [] for k in kinds}
+        for st in state:
+            st["oa"] = qmm.operand(st["cx"], fmt, st["dx"]); st["ob"] = qmm.operand(st["cw"], fmt, st["dw"])
+
+        def timed(kind, record, fn):
+            if kind in record:
+                e0, e1 = event_pair()
+                e0.record(); fn(); e1.record()
+                events[kind].append((e0, e1))
+            else:
+                fn()
+
+        def step(record):
+            for st in state:
+                timed("scale", record, lambda: qmm.scale_multi(st["xw"], fmt, outs=[st["dx"], st["dw"]], workspace=st["ws"],
+                                                               out_ptrs=st["d_ptrs"]))
+                timed("quantize", record, lambda: qmm.quantize_multi(st["xw"], fmt, [st["dx"], st["dw"]],
+                                                                     outs=[st["cx"], st["cw"]], delta_ptrs=st["d_ptrs"],
+                                                                     out_ptrs=st["c_ptrs"]))
+                timed("gemm", record, lambda: qmm.gemm((st["cx"], st["oa"]), (st["cw"], st["ob"]), out=st["y"]))
+                timed("metric", record, lambda: qmm.metric(st["y"], st["y_ref"], out=st["m"], workspace=st["ws"]))
+
+        # Timed region: whole steps, with a pair of HIP events around every launch of the dominant kernel only (an
+        # event pair costs several us of stream time; around all 16 launches of a step it would add a tenth to it).
+        for _ in range(warmup):
+            step(())
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step(("gemm",))
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        for _ in range(steps):
+            step(("scale", "quantize", "metric"))
+        torch.cuda.synchronize()
+        per_kind_ms = {k: sum(a.elapsed_time(b) for a, b in v) / steps for k, v in events.items()}
+        g_ms = [a.elapsed_time(b) for a, b in events["gemm"]]       # launch order: step-major, op-minor
+        gemm_tflops = flops / (per_kind_ms["gemm"] * 1e-3) / 1e12
+        res = {"ms_per_step": dt / steps * 1e3, "value": flops / (dt / steps) / 1e12, "gemm_tflops": gemm_tflops,
+               "gemm_ms_per_launch": per_kind_ms["gemm"] / len(ops), "per_kind_ms": per_kind_ms,
+               "median_launch_ms_by_op": {st["op"].name: round(sorted(g_ms[i::len(ops)])[steps // 2], 4)
+                                          for i, st in enumerate(state)},
+               "nsr": {st["op"].name: float(st["m"][0].item() / st["m"][1].item()) for st in state}}
+        res["passes"] = {k: {"ms_per_step": round(per_kind_ms[k], 4),
+                             "GBps": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9, 1),
+                             "frac_hbm": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                         for k in ("scale", "quantize", "metric")}
+        return res
+
+    main_res = run_steps(args.format, args.steps, args.warmup)
+    fmt = qmm.FORMATS[args.format]
+    passes = main_res["passes"]
+    traffic = load_traffic(args.workload, args.format)
     roofline = {"bound": "mfma", "kernel": "gemm_stream_kernel (QKV, FFN1) + gemm_kernel (attn_out, FFN2): fp8/int8 MFMA, 4 launches per step",
-                "achieved": round(gemm_tflops, 1), "peak": PEAK[args.format], "unit": "TFLOP/s",
-                "frac": round(gemm_tflops / PEAK[args.format], 4),
-                "traffic": GEMM_TRAFFIC.get((args.workload, args.format)),
-                "avg_launch_ms": round(gemm_ms_per_launch, 4)}
-    g_ms = [a.elapsed_time(b) for a, b in events["gemm"]]       # launch order: step-major, op-minor
-    roofline["median_launch_ms_by_op"] = {st["op"].name: round(sorted(g_ms[i::len(ops)])[args.steps // 2], 4)
-                                          for i, st in enumerate(state)}
+                "achieved": round(main_res["gemm_tflops"], 1), "peak": PEAK[args.format], "unit": "TFLOP/s",
+                "frac": round(main_res["gemm_tflops"] / PEAK[args.format], 4),
+                "traffic": traffic, "avg_launch_ms": round(main_res["gemm_ms_per_launch"], 4),
+                "median_launch_ms_by_op": main_res["median_launch_ms_by_op"]}
+    out = {"metric": "quantized GEMM TFLOP/s (e4m3/int8) + metric-pass GB/s, % of MI355X peak",
+           "value": round(main_res["value"], 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(main_res["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": DTYPE[args.format], "data": "synthetic",
+           "config": {"workload": f"{args.workload}: scale+quantize+gemm+descale+metric over QKV, attn_out, FFN1, FFN2 "
+                                  f"(tokens {dims['tokens']}, hidden {dims['hidden']}, ffn {dims['ffn']}), "
+                                  f"{args.format} per-tensor, bf16 out, reference product precomputed",
+                      "flops_per_step": flops},
+           "roofline": roofline, "passes": passes, "gemm_tflops": round(main_res["gemm_tflops"], 1), "nsr": main_res["nsr"]}
+    if args.no_extras:
+        out["cpu_baseline"] = None
+        print(json.dumps(out))
+        return
+
+    # ---- the tensor-moments pass (not a step of the quantized product: it characterises the operands beforehand) over
+    #      the same X and W, an event pair around the two calls of an op
+    mom = torch.empty(8, dtype=torch.float64, device=dev)
+    mom_ev = []
+    for _ in range(args.steps):
+        for st in state:
+            e0, e1 = event_pair()
+            e0.record(); qmm.moments(st["x"], out=mom, workspace=st["ws"]); qmm.moments(st["w"], out=mom, workspace=st["ws"]); e1.record()
+            mom_ev.append((e0, e1))
+    torch.cuda.synchronize()
+    mom_ms = sum(a.elapsed_time(b) for a, b in mom_ev) / args.steps
+    passes["moments"] = {"ms_per_step": round(mom_ms, 4), "GBps": round(algo_bytes["moments"] / (mom_ms * 1e-3) / 1e9, 1),
+                         "frac_hbm": round(algo_bytes["moments"] / (mom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
     # ---- what the matrix units sustain on these very codes with no memory traffic (and on constant codes): the
     #      chip's clock under matrix load is set by power, which depends on the operand bytes
     n_cu = torch.cuda.get_device_properties(0).multi_processor_count
@@ -162,7 +221,7 @@ def main():
     def mfma_only(codes):
         ts = []
         for _ in range(4):       # about 1 ms each, so that dispatch latency does not count
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0, e1 = event_pair()
             e0.record(); _, fl = qmm.mfma_rate(codes, fmt, fmt, rounds=1000, workgroups=n_cu, sink=sink); e1.record()
             torch.cuda.synchronize(); ts.append(e0.elapsed_time(e1))
         return fl / (sorted(ts[1:])[1] * 1e-3) / 1e12
@@ -174,15 +233,14 @@ def main():
     tiny = torch.zeros(1, device=dev)
     ov = []
     for _ in range(20):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0, e1 = event_pair()
         e0.record(); tiny.add_(1.0); e1.record(); torch.cuda.synchronize(); ov.append(e0.elapsed_time(e1))
     roofline["event_pair_around_one_element_kernel_ms"] = round(sorted(ov)[len(ov) // 2], 4)
     roofline["mfma_only_tflops"] = {"workload_codes": round(mfma_codes, 1), "constant_codes": round(mfma_const, 1)}
-    roofline["frac_of_mfma_only_on_workload_codes"] = round(gemm_tflops / mfma_codes, 4)
+    roofline["frac_of_mfma_only_on_workload_codes"] = round(main_res["gemm_tflops"] / mfma_codes, 4)
+
     # ---- context only, no part of the path: the vendor library's FP8 GEMM (torch._scaled_mm, i.e. hipBLASLt) on this
-    #      step's own code matrices with unit scales and bf16 output.  Ten launches back to back per op between one
-    #      event pair: its dispatch through torch costs more host time than ours, and timed launch by launch that
-    #      would be charged to its kernel (its kernel time by rocprofv3 is in profiles/).
+    #      step's own code matrices with unit scales and bf16 output, ten launches back to back per event pair
     def library_context():
         if fmt == qmm.INT8:
             return None
@@ -192,18 +250,9 @@ def main():
             total_ms, per_op = 0.0, {}
             for st in state:
                 a, b = st["cx"][0].view(dt8), st["cw"][0].view(dt8)
-                ts = []
-                for it in range(4):
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    for _ in range(10):
-                        torch._scaled_mm(a, b.t(), scale_a=one, scale_b=one, out_dtype=torch.bfloat16)
-                    e1.record()
-                    torch.cuda.synchronize()
-                    if it >= 1:
-                        ts.append(e0.elapsed_time(e1) / 10)
-                per_op[st["op"].name] = round(sorted(ts)[len(ts) // 2], 4)
-                total_ms += per_op[st["op"].name]
+                ms = back_to_back_ms(lambda k: torch._scaled_mm(a, b.t(), scale_a=one, scale_b=one, out_dtype=torch.bfloat16))
+                per_op[st["op"].name] = round(ms, 4)
+                total_ms += ms
             return {"what": "torch._scaled_mm (hipBLASLt) on the same codes, 10 launches back to back per event pair",
                     "tflops": round(flops / (total_ms * 1e-3) / 1e12, 1), "ms_per_launch": per_op}
         except Exception as e:          # the library may lack the call: the context line is then left out
@@ -213,18 +262,9 @@ def main():
     def own_back_to_back():
         total_ms, per_op = 0.0, {}
         for st in state:
-            ts = []
-            for it in range(4):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for _ in range(10):
-                    qmm.gemm((st["cx"], st["oa"]), (st["cw"], st["ob"]), out=st["y"])
-                e1.record()
-                torch.cuda.synchronize()
-                if it >= 1:
-                    ts.append(e0.elapsed_time(e1) / 10)
-            per_op[st["op"].name] = round(sorted(ts)[len(ts) // 2], 4)
-            total_ms += per_op[st["op"].name]
+            ms = back_to_back_ms(lambda k: qmm.gemm((st["cx"], st["oa"]), (st["cw"], st["ob"]), out=st["y"]))
+            per_op[st["op"].name] = round(ms, 4)
+            total_ms += ms
         return {"what": "qmm_gemm timed the same way (10 launches back to back per event pair)",
                 "tflops": round(flops / (total_ms * 1e-3) / 1e12, 1), "ms_per_launch": per_op}
     roofline["gemm_back_to_back"] = own_back_to_back()
@@ -232,38 +272,46 @@ def main():
     # the same product with the noise-to-signal sums taken in its epilogue (qmm_gemm_nsr), next to the product
     # followed by the full metric pass, both ten launches back to back per event pair
     def fused_nsr_context():
-        def ms_of(fn):
-            ts = []
-            for it in range(4):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for _ in range(10):
-                    fn()
-                e1.record()
-                torch.cuda.synchronize()
-                if it >= 1:
-                    ts.append(e0.elapsed_time(e1) / 10)
-            return sorted(ts)[len(ts) // 2]
         o2 = torch.empty(2, dtype=torch.float64, device=dev)
         ws = torch.empty(4 << 20, dtype=torch.uint8, device=dev)
         fused, separate = {}, {}
         for st in state:
-            fused[st["op"].name] = round(ms_of(lambda: qmm.gemm_nsr((st["cx"], st["oa"]), (st["cw"], st["ob"]), st["y_ref"][0],
-                                                                    out=st["y"], out2=o2, workspace=ws)), 4)
-            separate[st["op"].name] = round(ms_of(lambda: (qmm.gemm((st["cx"], st["oa"]), (st["cw"], st["ob"]), out=st["y"]),
-                                                           qmm.metric(st["y"], st["y_ref"], out=st["m"], workspace=st["ws"]))), 4)
+            fused[st["op"].name] = round(back_to_back_ms(lambda k: qmm.gemm_nsr((st["cx"], st["oa"]), (st["cw"], st["ob"]), st["y_ref"][0],
+                                                                                out=st["y"], out2=o2, workspace=ws)), 4)
+            separate[st["op"].name] = round(back_to_back_ms(lambda k: (qmm.gemm((st["cx"], st["oa"]), (st["cw"], st["ob"]), out=st["y"]),
+                                                                       qmm.metric(st["y"], st["y_ref"], out=st["m"], workspace=st["ws"]))), 4)
         return {"what": "qmm_gemm_nsr (two sums of the noise-to-signal ratio in the epilogue) against qmm_gemm + qmm_metric "
                         "(all 16 fields), ms per op", "gemm_nsr": fused, "gemm_then_metric": separate}
     roofline["fused_nsr"] = fused_nsr_context()
-    passes = {k: {"ms_per_step": round(per_kind_ms[k], 4),
-                  "GBps": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9, 1),
-                  "frac_hbm": round(algo_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-              for k in ("scale", "quantize", "metric", "moments")}
-    nsr = {st["op"].name: float(st["m"][0].item() / st["m"][1].item()) for st in state}
 
     # ---- the memory-bound passes on the step's largest tensors alone, free of launch latency: ten launches back to
     #      back per event pair, rotating over three copies of the operand (more bytes than the 256 MB memory-side
-    #      cache holds, so every launch reads HBM); the metric's inputs are larger than that cache by themselves
+    #      cache holds, so every launch reads HBM); the metric's inputs are larger than that cache by themselves.
+    #      Next to them the ceilings: a plain read and a plain copy kernel (qmm_hbm_rate) over three rotating 256 MiB buffers.
+    def rate(nbytes, fn, ceiling=None):
+        ms = back_to_back_ms(lambda k: fn(k % 3))
+        r = {"bytes_per_launch": nbytes, "ms_per_launch": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+             "frac_hbm": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        if ceiling:
+            r["frac_of_measured_ceiling"] = round(r["GBps"] / ceiling, 4)
+        return r
+
+    def ceilings():
+        sk = torch.empty(1024 * 256, dtype=torch.int32, device=dev)
+        def bufs(nbytes, count):
+            return [torch.full((nbytes,), i + 1, dtype=torch.uint8, device=dev) for i in range(count)]
+        small = bufs(128 << 20, 3)                          # the size of the step's largest X
+        dsts = [torch.empty(128 << 20, dtype=torch.uint8, device=dev) for _ in range(3)]
+        rd128 = rate(128 << 20, lambda k: qmm.hbm_rate(small[k], None, 1024, sk))
+        cp128 = rate(2 * (128 << 20), lambda k: qmm.hbm_rate(small[k], dsts[k], 1024, sk))
+        del dsts
+        large = bufs(384 << 20, 3)                          # the bytes one metric launch reads (Y bf16 + Y_ref)
+        rd384 = rate(384 << 20, lambda k: qmm.hbm_rate(large[k], None, 1024, sk))
+        return {"what": "plain streaming kernels (qmm_hbm_rate, 1024 workgroups, 16-byte streaming loads / stores) over three "
+                        "rotating buffers of the passes' own sizes, 10 launches back to back per event pair; copy counts bytes "
+                        "read + written", "read_128MiB": rd128, "read_384MiB": rd384, "copy_128MiB": cp128}
+    ceil = ceilings()
+
     def passes_on_largest():
         big_x = max(state, key=lambda st: st["x"].numel())
         xs = [big_x["x"]] + [big_x["x"].clone() for _ in range(2)]
@@ -272,51 +320,104 @@ def main():
         nx, ny = big_x["x"].numel(), big_y["y"].numel()
         ws, dx, m = big_x["ws"], big_x["dx"], big_y["m"]
         qmm.scale(xs[0], 1, fmt, out=dx, workspace=ws)
-
-        def rate(nbytes, fn):
-            ts = []
-            for it in range(4):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for k in range(10):
-                    fn(k % 3)
-                e1.record()
-                torch.cuda.synchronize()
-                if it >= 1:
-                    ts.append(e0.elapsed_time(e1) / 10)
-            ms = sorted(ts)[len(ts) // 2]
-            return {"bytes_per_launch": nbytes, "ms_per_launch": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
-                    "frac_hbm": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         return {"what": "largest X of the step (scale, quantize, moments) and largest Y (metric), 10 launches back to back per "
-                        "event pair, operands rotated over 3 copies",
-                "scale": rate(2 * nx, lambda k: qmm.scale(xs[k], 1, fmt, out=dx, workspace=ws)),
-                "quantize": rate(3 * nx, lambda k: qmm.quantize(xs[k], 1, fmt, dx, out=cs[k])),
-                "metric": rate(6 * ny, lambda k: qmm.metric(big_y["y"], big_y["y_ref"], out=m, workspace=ws)),
-                "moments": rate(2 * nx, lambda k: qmm.moments(xs[k], out=mom, workspace=ws))}
+                        "event pair, operands rotated over 3 copies; frac_of_measured_ceiling is against the plain read kernel on "
+                        "buffers of the same size (quantize: against the plain copy kernel)",
+                "scale": rate(2 * nx, lambda k: qmm.scale(xs[k], 1, fmt, out=dx, workspace=ws), ceil["read_128MiB"]["GBps"]),
+                "quantize": rate(3 * nx, lambda k: qmm.quantize(xs[k], 1, fmt, dx, out=cs[k]), ceil["copy_128MiB"]["GBps"]),
+                "metric": rate(6 * ny, lambda k: qmm.metric(big_y["y"], big_y["y_ref"], out=m, workspace=ws), ceil["read_384MiB"]["GBps"]),
+                "moments": rate(2 * nx, lambda k: qmm.moments(xs[k], out=mom, workspace=ws), ceil["read_128MiB"]["GBps"])}
     passes["largest_tensors"] = passes_on_largest()
+    out["ceilings"] = ceil
+
+    # ---- the same step in INT8 (the metric names e4m3 and int8)
+    if args.format == "e4m3" and args.workload == "bert_large_fwd":
+        r8 = run_steps("int8", max(5, args.steps // 2), 2)
+        out["int8"] = {"what": "the same step with INT8 operands (one step size per tensor), timed the same way",
+                       "value": round(r8["value"], 2), "unit": "TOP/s", "ms_per_step": round(r8["ms_per_step"], 4),
+                       "roofline": {"bound": "mfma", "achieved": round(r8["gemm_tflops"], 1), "peak": PEAK["int8"], "unit": "TOP/s",
+                                    "frac": round(r8["gemm_tflops"] / PEAK["int8"], 4), "traffic": load_traffic(args.workload, "int8"),
+                                    "avg_launch_ms": round(r8["gemm_ms_per_launch"], 4),
+                                    "median_launch_ms_by_op": r8["median_launch_ms_by_op"]},
+                       "passes": r8["passes"], "nsr": r8["nsr"]}
+        out["ops"] = ops_table(torch, qmm, W, state, ops, cfg_no, back_to_back_ms, dev)
+        out["attention"] = attention_products(torch, qmm, W, back_to_back_ms, dev)
 
     # ---- the oracle timed on the host cores, on a bounded sample of the same workload
-    cpu = None
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(state, args.format)
-
-    out = {"metric": "quantized GEMM TFLOP/s (e4m3/int8) + metric-pass GB/s, % of MI355X peak",
-           "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": {"e4m3": "fp8_e4m3", "e5m2": "fp8_e5m2", "int8": "int8"}[args.format], "data": "synthetic",
-           "config": {"workload": f"{args.workload}: scale+quantize+gemm+descale+metric over QKV, attn_out, FFN1, FFN2 "
-                                  f"(tokens {dims['tokens']}, hidden {dims['hidden']}, ffn {dims['ffn']}), "
-                                  f"{args.format} per-tensor, bf16 out, reference product precomputed",
-                      "flops_per_step": flops},
-           "roofline": roofline, "passes": passes, "gemm_tflops": round(gemm_tflops, 1), "nsr": nsr,
-           "cpu_baseline": cpu}
+    out["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(state, args.format)
     print(json.dumps(out))
+
+
+def ops_table(torch, qmm, W, state, ops, cfg_no, back_to_back_ms, dev):
+    """Every product of the layer as the GEMM alone (codes in, bf16 out, 10 launches back to back per event pair):
+    forward Y = X W^T, dgrad dX = dY W, wgrad dW^T = dY^T X (both operands contract over the token axis: codes from the
+    transposing quantize); E4M3 with E5M2 gradients, and INT8; one step size per tensor / per channel."""
+    rows = []
+    for st in state:
+        op = st["op"]
+        dy = W.upstream_gradient(op, cfg_no).to(dev)
+        wt = st["w"].t().contiguous()
+        products = {"fwd": ((st["x"], 1), (st["w"], 1), False), "dgrad": ((dy, 1), (wt, 1), True), "wgrad": ((dy, 0), (st["x"], 0), True)}
+        for pname, ((a, a_axis), (b, b_axis), a_is_grad) in products.items():
+            for family in ("e4m3", "int8"):
+                fa = qmm.INT8 if family == "int8" else (qmm.E5M2 if a_is_grad else qmm.E4M3)
+                fb = qmm.INT8 if family == "int8" else qmm.E4M3
+                for per_channel in (False, True):
+                    (ca, oa), _ = qmm.quantized_operand(a, a_axis, fa, per_channel)
+                    (cb, ob), _ = qmm.quantized_operand(b, b_axis, fb, per_channel)
+                    M, K = ca.shape[1:]; N = cb.shape[1]
+                    y = torch.empty((1, M, N), dtype=torch.bfloat16, device=dev)
+                    ms = back_to_back_ms(lambda k: qmm.gemm((ca, oa), (cb, ob), out=y))
+                    tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+                    rows.append({"op": op.name, "product": pname, "M": M, "N": N, "K": K,
+                                 "formats": ("int8 x int8" if family == "int8" else ("e5m2 x e4m3" if a_is_grad else "e4m3 x e4m3")),
+                                 "step_sizes": "channel" if per_channel else "tensor", "ms": round(ms, 4),
+                                 "tflops": round(tf, 1), "frac_mfma_peak": round(tf / 5000.0, 4)})
+                    del ca, cb, y
+        del dy, wt
+    agg = {}
+    for r in rows:
+        key = f"{r['product']}/{r['formats']}/{r['step_sizes']}"
+        a = agg.setdefault(key, [0.0, 0.0])
+        a[0] += 2.0 * r["M"] * r["N"] * r["K"]; a[1] += r["ms"]
+    return {"what": "GEMM alone per product of one BERT-large layer, codes in, bf16 out, 10 launches back to back per event pair",
+            "rows": rows,
+            "layer_tflops": {k: round(v[0] / (v[1] * 1e-3) / 1e12, 1) for k, v in agg.items()}}
+
+
+def attention_products(torch, qmm, W, back_to_back_ms, dev):
+    """BERT-large attention (32 examples x 16 heads, sequence 512, head dimension 64), E4M3 with one step size per head:
+    Q K^T (512 matrices of 512 x 512 x 64) and P V (512 x 64 x 512).  Both are bound by their operand and output
+    streams, not by the matrix units: GB/s of codes in + Y out against 8 TB/s."""
+    batch, heads, seq, dim = 32, 16, 512, 64
+    q, k, v = W.attention_operands(batch, heads, seq, dim)
+    qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+    (cq, oq), _ = qmm.quantized_operand(qd, 1, qmm.E4M3, False, heads)
+    (ck, ok), _ = qmm.quantized_operand(kd, 1, qmm.E4M3, False, heads)
+    p = W.softmax_probabilities(qmm.reference_gemm(qd, kd), dim).contiguous()
+    (cp, op_), _ = qmm.quantized_operand(p, 1, qmm.E4M3, False, heads)
+    (cv, ov), _ = qmm.quantized_operand(vd, 0, qmm.E4M3, False, heads)
+    res = {"what": "GEMM alone, codes in, 10 launches back to back per event pair; bytes = codes of both operands + Y"}
+    nb = batch * heads
+    for name, a, b, m, n, kk, dts in (("qk_t", (cq, oq), (ck, ok), seq, seq, dim, (torch.bfloat16, torch.float32)),
+                                      ("p_v", (cp, op_), (cv, ov), seq, dim, seq, (torch.bfloat16,))):
+        for dt in dts:
+            y = torch.empty((nb, m, n), dtype=dt, device=dev)
+            ms = back_to_back_ms(lambda i: qmm.gemm(a, b, out=y))
+            nbytes = nb * ((m + n) * kk + m * n * y.element_size())
+            res[f"{name}_{'bf16' if dt == torch.bfloat16 else 'f32'}_out"] = {
+                "ms": round(ms, 4), "bytes": nbytes, "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                "frac_hbm": round(nbytes / (ms * 1e-3) / 1e9 / 8000.0, 4),
+                "tflops": round(2.0 * nb * m * n * kk / (ms * 1e-3) / 1e12, 1)}
+            del y
+    return res
 
 
 def cpu_baseline(state, fmt_name, rows_per_op=8192):
     """Time the oracle (as it stands) on `rows_per_op` seeded rows of every op: scale and quantize of those rows of X
     and of all of W, the product of those rows with all of W, descale and metric."""
     import numpy as np
+    import torch
     from oracle import oracle as O
     fmt = O.FORMATS[fmt_name]
     O.lib()
@@ -326,7 +427,7 @@ def cpu_baseline(state, fmt_name, rows_per_op=8192):
         op = st["op"]
         rng = np.random.default_rng(op.M + op.N)
         rows = np.sort(rng.choice(op.M, size=min(rows_per_op, op.M), replace=False))
-        xs = st["host_x"][torch_index(rows)].float().numpy()
+        xs = st["host_x"][torch.from_numpy(rows)].float().numpy()
         w = st["host_w"].float().numpy()
         dx = O.scale(xs, 1, fmt); dw = O.scale(w, 1, fmt)
         cx = O.quantize(xs, 1, fmt, dx); cw = O.quantize(w, 1, fmt, dw)
@@ -339,11 +440,6 @@ def cpu_baseline(state, fmt_name, rows_per_op=8192):
     return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": O.num_threads(), "kind": "oracle",
             "sample": f"{rows_per_op} seeded rows of X per op against all of W (4 ops), full path incl. reference product; "
                       f"{dt:.1f} s of CPU work"}
-
-
-def torch_index(rows):
-    import torch
-    return torch.from_numpy(rows)
 
 
 if __name__ == "__main__":

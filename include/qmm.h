@@ -13,7 +13,12 @@
  *
  * General rules
  *  - Every pointer named "device" is GPU memory owned by the caller; the
- *    library allocates nothing, keeps no state between calls and frees nothing.
+ *    library allocates nothing and frees nothing.  What it keeps between calls:
+ *    per GPU, the addresses of two arrays of its own device image (the scratch
+ *    of qmm_scale_static, and a ring of arrival counters that the single-launch
+ *    reductions of qmm_scale / qmm_scale_multi use and leave at zero; a call
+ *    takes the next slot of the ring, 1024 calls would have to be in flight for
+ *    two of them to meet on one), and which GPUs have had the kernels' LDS limit set.
  *    Descriptor structs (qmm_tensor, qmm_operand, qmm_granularity) are host memory
  *    and are read before the call returns.
  *  - Calls validate their arguments on the host, enqueue kernels on `stream`
@@ -154,7 +159,7 @@ qmm_status qmm_quantize(const qmm_tensor* x, qmm_format fmt, const qmm_granulari
  *               16-byte aligned.
  * When all tensors (at most 8) are single dense bfloat16 matrices in 16-byte aligned whole vectors with one step size
  * each (and, for quantize: contract_axis 1, cols a multiple of 16, round to nearest even), each call is one launch
- * (two for scale: maxima, then one fold workgroup per tensor) with the tensor index as a grid dimension, so that the
+ * (for scale too: each tensor's workgroup that finishes last folds its partial maxima) with the tensor index as a grid dimension, so that the
  * small tensors' latency-bound kernels run inside the large tensors' launches.  Otherwise the tensors are processed
  * one after the other by the single-tensor code, after every tensor's arguments have been checked (an argument
  * error in any of them is returned before anything is launched).  Errors as for the single-tensor calls; count = 0
@@ -300,6 +305,18 @@ qmm_status qmm_moments(const void* x, qmm_dtype dtype, int64_t n, double center,
  */
 qmm_status qmm_mfma_rate(qmm_format a_format, qmm_format b_format, const void* operand_bytes, int64_t nbytes,
                          int64_t rounds, int32_t workgroups, float* sink, double* flops_out, void* stream);
+
+/*
+ * qmm_hbm_rate -- measurement aid, not a step of the method: a plain streaming kernel over `nbytes` of device memory,
+ * the ceiling the memory-bound passes (steps 1, 2 and 6) are read against next to the datasheet bandwidth.
+ *   src     device, nbytes (a multiple of 16), 16-byte aligned; read once with streaming loads
+ *   dst     device, nbytes, 16-byte aligned: the bytes are copied there; or NULL: read only, folded into `sink`
+ *   sink    device, workgroups * 256 words, written when dst is NULL (keeps the loads alive); caller-owned
+ *   workgroups  grid size (1024 = four workgroups per CU, as the passes use)
+ * Asynchronous on `stream`; the caller times it and rotates buffers larger than the caches.
+ * Errors: QMM_ERR_NULL, QMM_ERR_SHAPE, QMM_ERR_ALIGN, QMM_ERR_LAUNCH.
+ */
+qmm_status qmm_hbm_rate(const void* src, void* dst, int64_t nbytes, int32_t workgroups, uint32_t* sink, void* stream);
 
 const char* qmm_status_string(qmm_status s);
 /* Version of this ABI (major*100 + minor). */

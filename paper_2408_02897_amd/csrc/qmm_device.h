@@ -232,6 +232,62 @@ QMM_DEV double wave_max_f64(double v)
     return v;
 }
 
+// ---------------------------------------------------------------------------
+// "The workgroup that arrives last folds the partial results": one launch per reduction instead of two.
+// A call takes one slot (per reduced tensor) of a ring of arrival counters that live in the library's device
+// image and are zero between calls; every workgroup publishes its partial result, counts itself in, and the one
+// that completes the count folds all partials in a fixed order (so results do not depend on which one it is),
+// then puts the counters back to zero.  Counting is in two levels -- workgroups of one residue class of
+// blockIdx mod 8 (the XCD a workgroup runs on under round-robin dispatch) share a counter, the last of each class
+// counts into the slot's first word -- so that no counter takes more than an eighth of the grid's arrivals, each in
+// a cache line of its own.  The ring has kArrivalSlots slots handed out round robin: two calls can only meet on
+// one slot if that many calls are issued while the first is still running.
+// ---------------------------------------------------------------------------
+constexpr int kArrivalSlots = 8192;
+constexpr int kArrivalStride = 32;                       // words between the counters of a slot: 128 bytes
+constexpr int kArrivalWords = 9 * kArrivalStride;        // per slot: the slot's counter + eight class counters
+qmm_status arrival_slots(int count, uint32_t** first);   // host: `count` consecutive slots (qmm_api.hip)
+
+// Partial results cross from one workgroup to another through device-coherent accesses (they bypass the per-XCD
+// caches), not through fences: a release fence writes back the whole L2 of the XCD, and a thousand workgroups doing
+// that cost more than the reduction itself.  publish_* stores and waits until the store has left the CU; the
+// arrival is counted afterwards in program order; the last workgroup reads with coherent_load.
+QMM_DEV void publish_u32(uint32_t* p, uint32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+QMM_DEV void publish_f64(double* p, double v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+QMM_DEV uint32_t coherent_load(const uint32_t* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+QMM_DEV double coherent_load(const double* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// Called by all threads of a workgroup after its partial results have been published; true, for every thread, in
+// the one workgroup of the `total` that arrives last.
+QMM_DEV bool arrive_last(uint32_t* slot, unsigned id, unsigned total)
+{
+    __shared__ int s_last;
+    __syncthreads();                 // every publishing thread of the workgroup has waited for its store
+    if (threadIdx.x == 0) {
+        int last = 0;
+        const unsigned cls = id & 7u, in_cls = (total - cls + 7u) >> 3, classes = total < 8u ? total : 8u;
+        uint32_t* c = slot + (1 + cls) * kArrivalStride;
+        if (__hip_atomic_fetch_add(c, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == in_cls - 1u) {
+            __hip_atomic_store(c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (__hip_atomic_fetch_add(slot, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == classes - 1u) {
+                __hip_atomic_store(slot, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                last = 1;
+            }
+        }
+        s_last = last;
+    }
+    __syncthreads();
+    return s_last != 0;
+}
+
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 inline qmm_status launch_status() { return hipGetLastError() == hipSuccess ? QMM_OK : QMM_ERR_LAUNCH; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

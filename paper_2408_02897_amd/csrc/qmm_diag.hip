@@ -69,10 +69,52 @@ mfma_rate_kernel(const uint8_t* __restrict__ operand_bytes, int64_t nbytes, int6
     sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// qmm_hbm_rate: the other measurement aid -- what a plain streaming kernel reaches on this part, against which the
+// scale / quantize / metric passes are read next to the datasheet's 8 TB/s.  Every thread keeps four 16-byte loads in
+// flight per trip and the grid sweeps the buffer front to back (the access pattern of the absmax kernel); with a
+// destination the vectors are stored as they arrive (a copy), without one they are folded into one word per thread.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256)
+hbm_rate_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t nvec, uint32_t* __restrict__ sink)
+{
+    const int64_t stride = (int64_t)gridDim.x * 1024;
+    u32x4 f = {0u, 0u, 0u, 0u};
+    for (int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x; base < nvec; base += stride) {
+        u32x4 v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t idx = base + i * 256;
+            v[i] = idx < nvec ? __builtin_nontemporal_load(src + idx) : f;
+        }
+        if (dst) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t idx = base + i * 256;
+                if (idx < nvec) __builtin_nontemporal_store(v[i], dst + idx);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) f |= v[i];
+        }
+    }
+    if (!dst) sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = f[0] | f[1] | f[2] | f[3];
+}
+
 }  // namespace
 }  // namespace qmm
 
 using namespace qmm;
+
+extern "C" qmm_status qmm_hbm_rate(const void* src, void* dst, int64_t nbytes, int32_t workgroups, uint32_t* sink, void* stream)
+{
+    if (!src || (!dst && !sink)) return QMM_ERR_NULL;
+    if (nbytes < 0 || workgroups < 1) return QMM_ERR_SHAPE;
+    if (nbytes % 16 != 0 || !aligned16(src) || (dst && !aligned16(dst))) return QMM_ERR_ALIGN;
+    if (nbytes == 0) return QMM_OK;
+    hbm_rate_kernel<<<workgroups, 256, 0, as_stream(stream)>>>(static_cast<const u32x4*>(src), static_cast<u32x4*>(dst),
+                                                              nbytes / 16, sink);
+    return launch_status();
+}
 
 extern "C" qmm_status qmm_mfma_rate(qmm_format a_format, qmm_format b_format, const void* operand_bytes, int64_t nbytes,
                                     int64_t rounds, int32_t workgroups, float* sink, double* flops_out, void* stream)

@@ -1599,9 +1599,10 @@ gemm_stream_kernel(GemmArgs g)
 // An output at most 64 wide or high (attention: probabilities x values, N = head dimension) makes the product
 // HBM-bound: the long operand is read exactly once and nothing of it is reused, so staging it in LDS buys nothing,
 // while a 128 x 128 tile wastes half its columns and its ring admits two workgroups per CU at most.  Here a
-// wavefront loads the fragments of its 64 x 64 block straight from global memory into registers (a lane fetches 32
-// (FP8) or 64 contiguous bytes of a row per slab: whole 128-byte lines per row across the lanes; which K bytes a
-// lane holds only has to agree between the two operands), with no barrier and no LDS, so a dozen wavefronts per
+// wavefront loads the fragments of its 64 x 64 block straight from global memory into registers (a lane fetches two
+// 16-byte pieces (FP8) or 64 contiguous bytes (INT8) of a row per slab: whole 128-byte lines per row across the
+// lanes; which K bytes a lane holds has to agree between the two operands, and for FP8 it is the LDS kernels'
+// assignment so that the accumulators come out the same), with no barrier and no LDS, so a dozen wavefronts per
 // CU overlap each other's loads and stores.  The four wavefronts of a workgroup lie along the long side of the
 // output (blocks of 32 rows, i.e. twice the wavefronts, were slower: every wavefront re-reads the short operand).
 // Accumulator and store layout are those of gemm_kernel (a lane owns TILES_N consecutive columns of a row).
@@ -1642,10 +1643,13 @@ gemm_direct_kernel(GemmArgs g)
     const int64_t m_base = tile_m * BM + wm * WM, n_base = tile_n * BN + wn * WN;
     if (m_base >= g.M || n_base >= g.N) return;          // nothing of this wavefront's block lies inside the output
 
-    // lane (r, h): row r of an operand block; K bytes [W*h, W*h + W) of a slab, W = 32 (FP8: h = 0..3) or 64 (h = 0, 1)
+    // lane (r, h): row r of an operand block.  FP8 (h = 0..3): K bytes [16 h, 16 h + 16) and [64 + 16 h, 64 + 16 h + 16)
+    // of a slab, the assignment of the LDS kernels' fragments -- the matrix instruction adds its operand registers up in
+    // a fixed order, so with the same assignment every kernel returns the same accumulators for the same codes (and a
+    // load instruction covers 64 contiguous bytes of each row).  INT8 (h = 0, 1): K bytes [64 h, 64 h + 64).
     const int frow = lane & (R - 1);
     const int fsel = F8 ? (lane >> 4) : (lane >> 5);
-    const int kofs = fsel * (F8 ? 32 : 64);
+    const int kofs = fsel * (F8 ? 16 : 64);
     const int rowbytes = (int)g.rowbytes;
     const uint8_t* a_rows[BLOCKS_M];
     const uint8_t* b_rows[TILES_N];
@@ -1677,7 +1681,7 @@ gemm_direct_kernel(GemmArgs g)
     };
     auto load_frags = [&](const uint8_t* row_ptr, int k0, Frag (&f)[KS]) {
         if constexpr (F8) {
-            const v4i p0 = load16(row_ptr, k0), p1 = load16(row_ptr, k0 + 16);
+            const v4i p0 = load16(row_ptr, k0), p1 = load16(row_ptr, k0 + 64);
             f[0] = v8i{p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
         } else {
 #pragma unroll

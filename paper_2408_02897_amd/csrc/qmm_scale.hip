@@ -2,9 +2,11 @@
 // Methodology bullets on scale granularity and on aligning the absmax with the
 // format maximum).  HBM-bound: every element is read once (2 B for bfloat16),
 // the maximum is taken on magnitude bit patterns (exact, order-free), partial
-// maxima go to the workspace and a second small kernel folds them per group
-// and does the one division.  Two phases, no atomics, so the result does not
-// depend on launch geometry.
+// maxima go to the workspace and are folded per group, followed by the one
+// division: by a second small kernel, or -- dense tensors with one step size,
+// from 32 MB, and the several-tensors call -- by the workgroup that finishes
+// last (one launch).  The maximum is order-free, so the result does not depend
+// on launch geometry or on which workgroup folds.
 #include <algorithm>
 #include <atomic>
 #include "qmm_device.h"
@@ -48,15 +50,34 @@ QMM_DEV uint32_t finish_bf16(const u16x2 (&m)[4])
     return r << 16;   // bfloat16 magnitude -> binary32 magnitude bits
 }
 
-// Dense matrix (row_stride == cols), bfloat16, 16-byte vectors: grid (nblk, batch).
+// The fold of a tensor's partial maxima by the workgroup that arrived last: all of them are one scale group.
+QMM_DEV void fold_all_partials(const uint32_t* partial, int64_t count, float qmax, float* delta)
+{
+    uint32_t v[4] = {0u, 0u, 0u, 0u}, m = 0;
+    int64_t i = threadIdx.x;
+    for (; i + 3 * kThreads < count; i += 4 * kThreads) {         // four requests in flight
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = coherent_load(partial + i + k * kThreads);
+        m = max(max(m, max(v[0], v[1])), max(v[2], v[3]));
+    }
+    for (; i < count; i += kThreads) m = max(m, coherent_load(partial + i));
+    m = block_max_u32(m);
+    if (threadIdx.x == 0) delta[0] = delta_from_absmax_bits(m, qmax);
+}
+
+// Dense matrix (row_stride == cols), bfloat16, 16-byte vectors: grid (nblk, batch).  With `slot` (one scale group
+// for the whole batch) the workgroup that arrives last folds the partial maxima and writes the step size.
 __global__ void __launch_bounds__(kThreads)
-absmax_flat_bf16(const uint16_t* __restrict__ x, int64_t batch_stride, int64_t nvec, uint32_t* __restrict__ partial)
+absmax_flat_bf16(const uint16_t* __restrict__ x, int64_t batch_stride, int64_t nvec, uint32_t* __restrict__ partial,
+                 uint32_t* __restrict__ slot, float qmax, float* __restrict__ delta)
 {
     const u32x4* p = reinterpret_cast<const u32x4*>(x + (int64_t)blockIdx.y * batch_stride);
     u16x2 m[4] = {};
     // A workgroup takes four consecutive 4 KB pieces per trip and the grid sweeps the tensor front to back: the
     // four loads a thread has in flight are then neighbours in memory.  (With the loads a whole grid stride apart
-    // the same kernel reads a large tensor up to 25 % slower: four distant streams per thread.)
+    // the same kernel reads a large tensor up to 25 % slower: four distant streams per thread.)  Ordinary loads on
+    // purpose: streaming loads make this pass 7 % faster on a 134 MB tensor (23.0 against 24.6 us), but the quantize
+    // pass that follows then finds less of the tensor in the memory-side cache and loses twice that.
     const int64_t stride = (int64_t)gridDim.x * kThreads * 4;
     int64_t i = (int64_t)blockIdx.x * kThreads * 4 + threadIdx.x;
     for (; i + 3 * kThreads < nvec; i += stride) {
@@ -70,7 +91,14 @@ absmax_flat_bf16(const uint16_t* __restrict__ x, int64_t batch_stride, int64_t n
             if (i + u * kThreads < nvec) fold_bf16x8(p[i + u * kThreads], m);
     }
     const uint32_t r = block_max_u32(finish_bf16(m));
-    if (threadIdx.x == 0) partial[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = r;
+    const unsigned id = blockIdx.y * gridDim.x + blockIdx.x, total = gridDim.x * gridDim.y;
+    if (threadIdx.x == 0) {
+        if (slot) publish_u32(partial + id, r); else partial[id] = r;
+    }
+    if (slot && arrive_last(slot, id, total)) {
+        __syncthreads();                         // block_max_u32's shared words are reused by the fold
+        fold_all_partials(partial, total, qmax, delta);
+    }
 }
 
 // Several dense bfloat16 tensors, one step size each, in one launch (qmm_scale_multi): blockIdx.y picks the tensor,
@@ -83,6 +111,8 @@ struct MultiFlat {
     uint32_t* partial[kMaxMulti];
     float* delta[kMaxMulti];
     int nblk[kMaxMulti];
+    uint32_t* slots;                // kMaxMulti consecutive slots of arrival counters, one per tensor
+    float qmax;
 };
 __global__ void __launch_bounds__(kThreads)
 absmax_flat_multi(MultiFlat a)
@@ -105,26 +135,12 @@ absmax_flat_multi(MultiFlat a)
             if (i + u * kThreads < nvec) fold_bf16x8(p[i + u * kThreads], m);
     }
     const uint32_t r = block_max_u32(finish_bf16(m));
-    if (threadIdx.x == 0) a.partial[t][blockIdx.x] = r;
-}
-// one workgroup per tensor: at most kMaxFlatBlocks partial maxima, all requested before folding
-__global__ void __launch_bounds__(kThreads)
-finalize_multi(MultiFlat a, float qmax)
-{
-    const int t = blockIdx.x;
-    const uint32_t* partial = a.partial[t];
-    const int nblk = a.nblk[t];
-    uint32_t v[kMaxFlatBlocks / kThreads];
-#pragma unroll
-    for (int k = 0; k < kMaxFlatBlocks / kThreads; ++k) {
-        const int b = threadIdx.x + k * kThreads;
-        v[k] = b < nblk ? partial[b] : 0u;
+    if (threadIdx.x == 0) publish_u32(a.partial[t] + blockIdx.x, r);
+    // the tensor's last workgroup folds its partial maxima (at most kMaxFlatBlocks) and writes its step size
+    if (arrive_last(a.slots + (size_t)t * kArrivalWords, blockIdx.x, (unsigned)nblk)) {
+        __syncthreads();
+        fold_all_partials(a.partial[t], nblk, a.qmax, a.delta[t]);
     }
-    uint32_t m = 0;
-#pragma unroll
-    for (int k = 0; k < kMaxFlatBlocks / kThreads; ++k) m = max(m, v[k]);
-    m = block_max_u32(m);
-    if (threadIdx.x == 0) a.delta[t][0] = delta_from_absmax_bits(m, qmax);
 }
 
 template <typename T> QMM_DEV uint32_t mag_bits(T v);
@@ -423,10 +439,18 @@ extern "C" qmm_status qmm_scale(const qmm_tensor* x, qmm_format fmt, const qmm_g
                                  x->batch == g->batch_groups && g->batch_inner <= 1;
     if (nelem > 0) {
         switch (p.kind) {
-        case Plan::FLAT:
+        case Plan::FLAT: {
+            // One scale group for the whole batch and a large tensor: one launch, the workgroup that arrives last folds.
+            // (Publishing, counting and the coherent reads of the fold are a chain of device-wide round trips of
+            // 2-3 us each: about 11 us for a tensor of any size up to 32 MB, against 9-10 us for two small launches;
+            // from 32 MB on the single launch wins, 25 us against 27 us at 134 MB.)
+            uint32_t* slot = nullptr;
+            if (g->batch_groups == 1 && nelem >= (int64_t(1) << 24) && arrival_slots(1, &slot) != QMM_OK) slot = nullptr;
             absmax_flat_bf16<<<dim3(p.flat_blocks, (unsigned)x->batch), kThreads, 0, s>>>(
-                static_cast<const uint16_t*>(x->data), x->batch_stride, x->rows * x->cols / 8, partial);
+                static_cast<const uint16_t*>(x->data), x->batch_stride, x->rows * x->cols / 8, partial, slot, qmax, delta_out);
+            if (slot) return launch_status();
             break;
+        }
         case Plan::ROWS: {
             const int64_t total = x->batch * x->rows;
             float* direct = rows_are_groups ? delta_out : nullptr;
@@ -579,10 +603,10 @@ extern "C" qmm_status qmm_scale_multi(int32_t count, const qmm_tensor* x, qmm_fo
         max_blk = std::max(max_blk, p.flat_blocks);
         ws += multi_slice(x + t, g + t);
     }
-    const float qmax = fmt == QMM_FMT_INT8 ? 127.0f : (fmt == QMM_FMT_E4M3 ? 448.0f : 57344.0f);
+    a.qmax = fmt == QMM_FMT_INT8 ? 127.0f : (fmt == QMM_FMT_E4M3 ? 448.0f : 57344.0f);
+    const qmm_status sl = arrival_slots(count, &a.slots);
+    if (sl != QMM_OK) return sl;
     hipStream_t s = as_stream(stream);
     absmax_flat_multi<<<dim3((unsigned)max_blk, (unsigned)count), kThreads, 0, s>>>(a);
-    if (hipGetLastError() != hipSuccess) return QMM_ERR_LAUNCH;
-    finalize_multi<<<(unsigned)count, kThreads, 0, s>>>(a, qmax);
     return launch_status();
 }

@@ -15,7 +15,7 @@ RTNE, STOCHASTIC = 0, 1
 FORMATS = {"int8": INT8, "e4m3": E4M3, "e5m2": E5M2, "bf16": BF16}
 EXPORTS = ["qmm_num_scales", "qmm_scale_workspace_size", "qmm_scale", "qmm_scale_static", "qmm_quantize", "qmm_scale_multi_workspace_size", "qmm_scale_multi", "qmm_quantize_multi",
            "qmm_gemm_workspace_size",
-           "qmm_gemm", "qmm_gemm_nsr_workspace_size", "qmm_gemm_nsr", "qmm_metric_workspace_size", "qmm_metric", "qmm_dequantize", "qmm_moments_workspace_size", "qmm_moments", "qmm_mfma_rate", "qmm_status_string", "qmm_version"]
+           "qmm_gemm", "qmm_gemm_nsr_workspace_size", "qmm_gemm_nsr", "qmm_metric_workspace_size", "qmm_metric", "qmm_dequantize", "qmm_moments_workspace_size", "qmm_moments", "qmm_mfma_rate", "qmm_hbm_rate", "qmm_status_string", "qmm_version"]
 
 
 class QmmError(RuntimeError):
@@ -71,6 +71,7 @@ def lib():
         L.qmm_moments.restype = i32; L.qmm_moments.argtypes = [vp, i32, i64, ctypes.c_double, vp, vp, sz, vp]
         L.qmm_mfma_rate.restype = i32
         L.qmm_mfma_rate.argtypes = [i32, i32, vp, i64, i64, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.qmm_hbm_rate.restype = i32; L.qmm_hbm_rate.argtypes = [vp, vp, i64, i32, vp, vp]
         L.qmm_status_string.restype = ctypes.c_char_p; L.qmm_status_string.argtypes = [i32]
         L.qmm_version.restype = i32; L.qmm_version.argtypes = []
         _lib = L
@@ -334,6 +335,17 @@ def mfma_rate(codes, fmt_a, fmt_b, rounds=2000, workgroups=None, sink=None):
     _check(L.qmm_mfma_rate(fmt_a, fmt_b, codes.data_ptr(), codes.numel(), int(rounds), int(workgroups), sink.data_ptr(),
                            ctypes.byref(flops), _stream()), "qmm_mfma_rate")
     return sink, flops.value
+
+
+def hbm_rate(src, dst=None, workgroups=1024, sink=None):
+    """qmm_hbm_rate over the bytes of the contiguous device tensor src (copied to dst when given); returns the sink."""
+    L = lib()
+    assert src.is_contiguous() and src.is_cuda and (dst is None or (dst.is_contiguous() and dst.numel() * dst.element_size() == src.numel() * src.element_size()))
+    if sink is None:
+        sink = torch.empty(workgroups * 256, dtype=torch.int32, device=src.device)
+    _check(L.qmm_hbm_rate(src.data_ptr(), dst.data_ptr() if dst is not None else None, src.numel() * src.element_size(),
+                          int(workgroups), sink.data_ptr(), _stream()), "qmm_hbm_rate")
+    return sink
 
 
 METRIC_FIELDS = ("S_ee", "S_rr", "S_ae", "S_ar", "M_e", "M_r", "RE_sum", "RE_max", "RE_cnt",
