@@ -17,7 +17,8 @@ step in E4M3; the same line carries, measured after the timed region:
 Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_large_fwd|bert_base_fwd]
-                    [--format e4m3|e5m2|int8] [--no-cpu-baseline] [--no-extras]
+                    [--format e4m3|e5m2|int8] [--no-cpu-baseline] [--no-extras] [--full]
+The line on stdout is compact (numbers per section); every table goes to gpurun_out/bench_detail.json.
 """
 import argparse
 import json
@@ -54,6 +55,7 @@ def main():
     ap.add_argument("--format", default="e4m3", choices=["e4m3", "e5m2", "int8"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="only the timed step (what the profiling commands run)")
+    ap.add_argument("--full", action="store_true", help="print every table in the line instead of the compact form")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten plain device copies of 256 MiB (to scale the FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
@@ -189,13 +191,15 @@ def main():
            "value": round(main_res["value"], 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(main_res["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": DTYPE[args.format], "data": "synthetic",
-           "config": {"workload": f"{args.workload}: scale+quantize+gemm+descale+metric over QKV, attn_out, FFN1, FFN2 "
-                                  f"(tokens {dims['tokens']}, hidden {dims['hidden']}, ffn {dims['ffn']}), "
-                                  f"{args.format} per-tensor, bf16 out, reference product precomputed",
+           "config": {"workload": f"{args.workload} ({args.format}, per-tensor, bf16 out): scale+quantize+gemm+metric of QKV, "
+                                  f"attn_out, FFN1, FFN2; tokens {dims['tokens']}, hidden {dims['hidden']}, ffn {dims['ffn']}",
                       "flops_per_step": flops},
            "roofline": roofline, "passes": passes, "gemm_tflops": round(main_res["gemm_tflops"], 1), "nsr": main_res["nsr"]}
     if args.no_extras:
         out["cpu_baseline"] = None
+        if traffic:
+            roofline["traffic"] = traffic["read_bytes"] + traffic["write_bytes"]
+            roofline["traffic_detail"] = traffic
         print(json.dumps(out))
         return
 
@@ -345,7 +349,67 @@ def main():
 
     # ---- the oracle timed on the host cores, on a bounded sample of the same workload
     out["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(state, args.format)
-    print(json.dumps(out))
+    if args.full:
+        print(json.dumps(out))
+        return
+    # Everything measured goes to a file; the ONE line on stdout carries the contract keys and the figures of each section
+    # as plain numbers (a few KB).
+    try:
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_detail.json"), "w") as f:
+            json.dump(out, f, indent=1)
+    except OSError:
+        pass
+    print(json.dumps(compact_line(out)))
+
+
+def compact_line(out):
+    """The printed line: contract keys unchanged; nested tables flattened to numbers."""
+    r = out["roofline"]
+    t = r.get("traffic") or {}
+    roof = {k: r[k] for k in ("bound", "kernel", "achieved", "peak", "unit", "frac", "avg_launch_ms")}
+    roof["traffic"] = (t["read_bytes"] + t["write_bytes"]) if t else None        # HBM bytes per launch, by counters
+    if t:
+        roof.update({"traffic_read_bytes": t["read_bytes"], "traffic_write_bytes": t["write_bytes"],
+                     "algorithmic_bytes": t["algorithmic_read_bytes"] + t["algorithmic_write_bytes"],
+                     "operand_reread_ratio": t.get("reread_ratio")})
+    roof["ms_by_op"] = r["median_launch_ms_by_op"]
+    roof.update({"event_pair_overhead_ms": r["event_pair_around_one_element_kernel_ms"],
+                 "mfma_only_tflops_workload_codes": r["mfma_only_tflops"]["workload_codes"],
+                 "mfma_only_tflops_constant_codes": r["mfma_only_tflops"]["constant_codes"],
+                 "frac_of_mfma_only_on_workload_codes": r["frac_of_mfma_only_on_workload_codes"],
+                 "gemm_back_to_back_tflops": r["gemm_back_to_back"]["tflops"],
+                 "vendor_library_gemm_tflops": (r["vendor_library_gemm"] or {}).get("tflops")})
+    line = {k: out[k] for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better",
+                                "scaling", "vs_baseline", "dtype", "data", "config")}
+    if "int8" in out:
+        i8 = out["int8"]
+        roof.update({"int8_achieved": i8["roofline"]["achieved"], "int8_frac": i8["roofline"]["frac"],
+                     "int8_step_value": i8["value"], "int8_ms_per_step": i8["ms_per_step"]})
+        t8 = i8["roofline"].get("traffic") or {}
+        if t8:
+            roof["int8_traffic"] = t8["read_bytes"] + t8["write_bytes"]
+    c = out["ceilings"]
+    roof.update({"hbm_read_ceiling_GBps": c["read_128MiB"]["GBps"], "hbm_read_ceiling_384MiB_GBps": c["read_384MiB"]["GBps"],
+                 "hbm_copy_ceiling_GBps": c["copy_128MiB"]["GBps"]})
+    line["roofline"] = roof
+    ps = out["passes"]
+    big = ps["largest_tensors"]
+    line["passes"] = {k: {"in_step_GBps": ps[k]["GBps"], "in_step_frac_hbm": ps[k]["frac_hbm"],
+                          "largest_tensor_GBps": big[k]["GBps"], "largest_tensor_frac_hbm": big[k]["frac_hbm"],
+                          "frac_of_measured_ceiling": big[k]["frac_of_measured_ceiling"]}
+                      for k in ("scale", "quantize", "metric", "moments")}
+    if "ops" in out:
+        line["layer_gemm_tflops"] = out["ops"]["layer_tflops"]       # product / formats / step sizes -> TFLOP/s of one layer
+        a = out["attention"]
+        line["attention"] = {k: {"ms": v["ms"], "GBps": v["GBps"], "frac_hbm": v["frac_hbm"]} for k, v in a.items() if k != "what"}
+    if "int8" in out:
+        line["int8_passes"] = {k: v["frac_hbm"] for k, v in out["int8"]["passes"].items()}
+    line["fused_nsr_ms"] = {"gemm_nsr": r["fused_nsr"]["gemm_nsr"], "gemm_then_metric": r["fused_nsr"]["gemm_then_metric"]}
+    line["nsr"] = {k: round(v, 6) for k, v in out["nsr"].items()}
+    line["detail"] = "gpurun_out/bench_detail.json (every table; --full prints it instead)"
+    line["cpu_baseline"] = out["cpu_baseline"]
+    return line
 
 
 def ops_table(torch, qmm, W, state, ops, cfg_no, back_to_back_ms, dev):
@@ -370,7 +434,7 @@ def ops_table(torch, qmm, W, state, ops, cfg_no, back_to_back_ms, dev):
                     ms = back_to_back_ms(lambda k: qmm.gemm((ca, oa), (cb, ob), out=y))
                     tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
                     rows.append({"op": op.name, "product": pname, "M": M, "N": N, "K": K,
-                                 "formats": ("int8 x int8" if family == "int8" else ("e5m2 x e4m3" if a_is_grad else "e4m3 x e4m3")),
+                                 "formats": ("int8" if family == "int8" else ("e5m2xe4m3" if a_is_grad else "e4m3")),
                                  "step_sizes": "channel" if per_channel else "tensor", "ms": round(ms, 4),
                                  "tflops": round(tf, 1), "frac_mfma_peak": round(tf / 5000.0, 4)})
                     del ca, cb, y
@@ -380,8 +444,10 @@ def ops_table(torch, qmm, W, state, ops, cfg_no, back_to_back_ms, dev):
         key = f"{r['product']}/{r['formats']}/{r['step_sizes']}"
         a = agg.setdefault(key, [0.0, 0.0])
         a[0] += 2.0 * r["M"] * r["N"] * r["K"]; a[1] += r["ms"]
-    return {"what": "GEMM alone per product of one BERT-large layer, codes in, bf16 out, 10 launches back to back per event pair",
-            "rows": rows,
+    # compact: one list per product (the JSON line stays a few KB)
+    return {"what": "GEMM alone per product of one BERT-large layer, codes in, bf16 out, 10 launches back to back per event pair; "
+                    "rows = [op, product, formats, step sizes, ms, TFLOP/s, fraction of 5.0 PFLOP/s]",
+            "rows": [[r["op"], r["product"], r["formats"], r["step_sizes"], r["ms"], r["tflops"], r["frac_mfma_peak"]] for r in rows],
             "layer_tflops": {k: round(v[0] / (v[1] * 1e-3) / 1e12, 1) for k, v in agg.items()}}
 
 
