@@ -146,3 +146,14 @@ def test_multi_tensor_argument_errors(L):
     assert L.qmm_quantize_multi(n, ts, qmm.E4M3, gs, ptrs, 5, 0, None, ptrs, None) == 3
     # tensors with NULL data go to the single-tensor code, which reports them
     assert L.qmm_quantize_multi(n, ts, qmm.E4M3, gs, ptrs, qmm.RTNE, 0, None, ptrs, None) == 1
+
+
+def test_measurement_aids_reject_bad_arguments(L):
+    fake = ctypes.c_void_p(0x1000)
+    assert L.qmm_hbm_rate(None, None, 1024, 64, fake, None) == 1            # no source
+    assert L.qmm_hbm_rate(fake, None, 1024, 64, None, None) == 1            # read-only needs a sink
+    assert L.qmm_hbm_rate(fake, None, -16, 64, fake, None) == 2
+    assert L.qmm_hbm_rate(fake, None, 1024, 0, fake, None) == 2
+    assert L.qmm_hbm_rate(fake, None, 1000, 64, fake, None) == 4            # not a multiple of 16 bytes
+    assert L.qmm_hbm_rate(ctypes.c_void_p(0x1008), None, 1024, 64, fake, None) == 4
+    assert L.qmm_hbm_rate(fake, None, 0, 64, fake, None) == 0               # nothing to do, nothing launched
