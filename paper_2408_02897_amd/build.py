@@ -47,7 +47,8 @@ def check_asm():
     registers, (3) no MFMA goes through v_accvgpr_mov copies inside the loops (at most one initialisation pass), (4) the
     kernels on the throughput path use no scratch memory, (5) the streaming kernel initialises no accumulator by a
     separate instruction and has no load the compiler knows of (outside the inline-assembly statements) behind its first MFMA (with stores outstanding the
-    compiler waits for such a load with vmcnt(0), i.e. for every store).  Returns a list of findings (empty = clean)."""
+    compiler waits for such a load with vmcnt(0), i.e. for every store), (6) the registers its inline-assembly loads fill without waiting (a tile's step
+    sizes) are touched by nothing before two step barriers have passed.  Returns a list of findings (empty = clean)."""
     os.makedirs(OBJDIR, exist_ok=True)
     asm = os.path.join(OBJDIR, "qmm_gemm.s")
     subprocess.run([HIPCC, *[f for f in FLAGS if f != "-fPIC"], "--cuda-device-only", "-S",
@@ -86,6 +87,19 @@ def check_asm():
                 findings.append(f"{nm}: {len(late)} loads behind the first MFMA, e.g. '{late[0][:60]}'")
             if body.count("v_accvgpr_write") or body.count("v_accvgpr_mov"):
                 findings.append(f"{nm}: accumulators written or moved by separate instructions")
+            # the step sizes requested behind a tile's first step are waited for by nobody: the next instruction that
+            # touches such a register (a copy the compiler made would be one) has to lie behind two step barriers
+            first_mfma = next(k for k, l in enumerate(instrs) if l.startswith("v_mfma"))
+            for k in range(first_mfma, len(instrs)):
+                m = re.match(r"global_load_dword v(\d+),", instrs[k])
+                if not m:
+                    continue
+                dst = int(m.group(1))
+                for d, q in enumerate(instrs[k + 1:]):
+                    if re.search(rf"\bv{dst}\b", q) or any(int(a) <= dst <= int(b) for a, b in re.findall(r"v\[(\d+):(\d+)\]", q)):
+                        if sum(1 for x in instrs[k + 1:k + 1 + d] if x.startswith("s_barrier")) < 2:
+                            findings.append(f"{nm}: v{dst}, loaded without a wait, is touched too early by '{q[:60]}'")
+                        break
         n_acc = 128 if ("ELi4ELi1ELi4E" in nm or "shortk" in nm) else 64
         if body.count("v_accvgpr_mov") > n_acc:
             findings.append(f"{nm}: {body.count('v_accvgpr_mov')} v_accvgpr_mov (accumulators copied around MFMAs)")

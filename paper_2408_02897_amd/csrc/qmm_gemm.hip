@@ -81,6 +81,7 @@ struct GemmArgs {
     const float* nsr_ref;             // NSR variant: high-precision product [batch][M][N], else null
     double* nsr_partial;              // NSR variant: per wavefront {sum (y - ref)^2, sum ref^2}
     double* nsr_out;                  // NSR variant: the two folded sums
+    int stagger;                      // gemm_stream_kernel: every other workgroup of an XCD starts this many sleeps late
 };
 
 // 16 bytes per lane from global memory into LDS: lane l lands at lds_unit + 16*l.
@@ -1197,6 +1198,14 @@ gemm_stream_kernel(GemmArgs g)
     const uint32_t stride = gridDim.x;
     uint32_t t_cur = blockIdx.x;
     if (t_cur >= total) return;
+    // Two phases.  Every workgroup has the same work, so left alone all 256 reach their tile boundaries together and
+    // 33 MB of output leave at once: a wavefront's copies behind its stores are only known to have landed when those
+    // stores have drained (one in-order counter), so the matrix units idle while memory takes the burst.  With every
+    // other workgroup of an XCD some 4 us behind, half of the chip stores while the other half multiplies.  Worth its
+    // idle start from four tiles per workgroup on (host); measured on 16384 x 4096 x 1024, launches back to back:
+    // 69 -> 62 us (more phases or other offsets: the same within noise).
+    if (g.stagger > 0 && ((blockIdx.x / kNumXcd) & 1u))
+        for (int i = 0; i < g.stagger; ++i) __builtin_amdgcn_s_sleep(8);       // 512 cycles each
     Tile cur = tile_of(t_cur);
 
     // ---- prologue of the stream: slab 0 of both operands, then what the steps before a tile's first step request
@@ -1222,6 +1231,8 @@ gemm_stream_kernel(GemmArgs g)
     // any other granularity: the step sizes are fetched per tile, in the epilogue
     const bool scales_in_loop = g.da_per_channel || g.db_per_channel || g.da_groups != 1 || g.db_groups != 1;
 
+    // step sizes of the current tile when they are not one per operand: rows lane and 64 + lane, the lane's columns
+    float sc_a0 = 0.0f, sc_a1 = 0.0f, sc_b0 = 0.0f, sc_b1 = 0.0f, sc_b2 = 0.0f, sc_b3 = 0.0f;
     int a_slot = 0, b_slot = 0;                // ring slots of the stream's current slab
     for (;;) {
         const uint32_t t_next = t_cur + stride;
@@ -1322,6 +1333,39 @@ gemm_stream_kernel(GemmArgs g)
         };
         using T = std::true_type; using F = std::false_type;
         step(0, T{}, T{}, F{});
+        // Step sizes per channel or batch group of this tile: requested here, behind the first step's wait (whose count
+        // is exact) and in front of the second step's copies, by loads the compiler does not see and nobody waits for:
+        // the second step's wait allows only its newest copies outstanding, so these have landed from then on, and
+        // they are first used in the epilogue.  Six registers across the tile (four with INT8).
+        if (scales_in_loop) {
+            const uint32_t ga = ((uint32_t)cur.bidx / (uint32_t)g.da_inner) % (uint32_t)g.da_groups;
+            const uint32_t gb = ((uint32_t)cur.bidx / (uint32_t)g.db_inner) % (uint32_t)g.db_groups;
+            int lane_s = lane;
+            asm volatile("" : "+v"(lane_s));
+            const float* pa = g.da + (g.da_per_channel ? (int64_t)ga * g.M + cur.m0 + wm * WM + lane_s : (int64_t)ga);
+            const float* pa1 = g.da_per_channel ? pa + 64 : pa;
+            const float* pb = g.db + (g.db_per_channel ? (int64_t)gb * g.N + cur.n0 + wn * WN + TILES_N * (lane_s & (R - 1)) : (int64_t)gb);
+#if defined(__HIP_DEVICE_COMPILE__)
+            // (in-out operands: the loads write the very registers that are carried round the tile loop, so that no copy of
+            // a register that has not landed yet is made behind them; build --check-asm looks for such reads)
+            asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %3, off"
+                         : "+v"(sc_a0), "+v"(sc_a1) : "v"(pa), "v"(pa1));
+            // (one register per load -- a vector's registers were copied behind the load -- and one statement whatever the
+            // granularity -- registers that met behind a branch were copied there: with one step size per group the
+            // lane's four loads read the same word)
+            const float* pb1 = g.db_per_channel ? pb + 1 : pb;
+            if constexpr (F8) {
+                const float* pb2 = g.db_per_channel ? pb + 2 : pb;
+                const float* pb3 = g.db_per_channel ? pb + 3 : pb;
+                asm volatile("global_load_dword %0, %4, off\n\tglobal_load_dword %1, %5, off\n\t"
+                             "global_load_dword %2, %6, off\n\tglobal_load_dword %3, %7, off"
+                             : "+v"(sc_b0), "+v"(sc_b1), "+v"(sc_b2), "+v"(sc_b3) : "v"(pb), "v"(pb1), "v"(pb2), "v"(pb3));
+            } else {
+                asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %3, off"
+                             : "+v"(sc_b0), "+v"(sc_b1) : "v"(pb), "v"(pb1));
+            }
+#endif
+        }
         // the next tile's coordinates: a few hundred scalar and vector instructions (divisions), here behind matrix
         // instructions already issued rather than between the epilogue and the first of them
         if (has_next) nxt = tile_of(t_next);
@@ -1409,181 +1453,21 @@ gemm_stream_kernel(GemmArgs g)
             before_stores();
             store_tile([&](int ia, int r, int tt) -> float { return (accumulator(ia, r, tt) * delta_a) * delta_b; });
         } else {
-            // Step sizes per channel or per batch group: fetched here, by loads the compiler does not see, waited for at
-            // once (one statement: the registers are valid when it ends) and in front of the copies for the next tile,
-            // so that the wait covers only copies requested a step ago.  About half a microsecond per tile, most of it
-            // behind the last block's matrix instructions still in the pipe.
+            // Step sizes per channel or per batch group were requested behind the tile's first step (above) and have
+            // landed long since: every later step's wait left only operations newer than them outstanding.  A lane
+            // holds the step sizes of rows lane and 64 + lane of the wavefront's 128; the one for an accumulator's row
+            // comes across the lanes (ds_bpermute: no LDS memory, no vector-memory operation between the stores).
             auto finish = [&](auto a_tag, auto b_tag) {
                 constexpr bool A_PC = decltype(a_tag)::value, B_PC = decltype(b_tag)::value;
-                constexpr int NRA = F8 ? 8 : 16;                   // 16-byte loads of four consecutive rows' step sizes
-                typedef float f2v __attribute__((ext_vector_type(2)));
-                using ColT = typename std::conditional<F8, v4f, f2v>::type;
-                v4f ra[A_PC ? NRA : 1];
-                ColT cb;
-                float ra_s = 1.0f, cb_s = 1.0f;
-                const uint32_t ga = ((uint32_t)cur.bidx / (uint32_t)g.da_inner) % (uint32_t)g.da_groups;
-                const uint32_t gb = ((uint32_t)cur.bidx / (uint32_t)g.db_inner) % (uint32_t)g.db_groups;
-                const float* pa = g.da + (A_PC ? (int64_t)ga * g.M + m_base + lane_row : (int64_t)ga);
-                const float* pb = g.db + (B_PC ? (int64_t)gb * g.N + n : (int64_t)gb);
-#if defined(__HIP_DEVICE_COMPILE__)
-                if constexpr (F8 && !A_PC && !B_PC) {
-                    asm volatile("global_load_dword %[r0], %[pa], off\n\t"
-                        "global_load_dword %[c0], %[pb], off\n\t"
-                        "s_waitcnt vmcnt(0)"
-                        : [r0] "=&v"(ra_s),
-                          [c0] "=&v"(cb_s)
-                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
-                }
-                if constexpr (F8 && !A_PC && B_PC) {
-                    asm volatile("global_load_dword %[r0], %[pa], off\n\t"
-                        "global_load_dwordx4 %[c0], %[pb], off\n\t"
-                        "s_waitcnt vmcnt(0)"
-                        : [r0] "=&v"(ra_s),
-                          [c0] "=&v"(cb)
-                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
-                }
-                if constexpr (F8 && A_PC && !B_PC) {
-                    asm volatile("global_load_dwordx4 %[r0], %[pa], off\n\t"
-                        "global_load_dwordx4 %[r1], %[pa], off offset:64\n\t"
-                        "global_load_dwordx4 %[r2], %[pa], off offset:128\n\t"
-                        "global_load_dwordx4 %[r3], %[pa], off offset:192\n\t"
-                        "global_load_dwordx4 %[r4], %[pa], off offset:256\n\t"
-                        "global_load_dwordx4 %[r5], %[pa], off offset:320\n\t"
-                        "global_load_dwordx4 %[r6], %[pa], off offset:384\n\t"
-                        "global_load_dwordx4 %[r7], %[pa], off offset:448\n\t"
-                        "global_load_dword %[c0], %[pb], off\n\t"
-                        "s_waitcnt vmcnt(0)"
-                        : [r0] "=&v"(ra[0]),
-                          [r1] "=&v"(ra[1]),
-                          [r2] "=&v"(ra[2]),
-                          [r3] "=&v"(ra[3]),
-                          [r4] "=&v"(ra[4]),
-                          [r5] "=&v"(ra[5]),
-                          [r6] "=&v"(ra[6]),
-                          [r7] "=&v"(ra[7]),
-                          [c0] "=&v"(cb_s)
-                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
-                }
-                if constexpr (F8 && A_PC && B_PC) {
-                    asm volatile("global_load_dwordx4 %[r0], %[pa], off\n\t"
-                        "global_load_dwordx4 %[r1], %[pa], off offset:64\n\t"
-                        "global_load_dwordx4 %[r2], %[pa], off offset:128\n\t"
-                        "global_load_dwordx4 %[r3], %[pa], off offset:192\n\t"
-                        "global_load_dwordx4 %[r4], %[pa], off offset:256\n\t"
-                        "global_load_dwordx4 %[r5], %[pa], off offset:320\n\t"
-                        "global_load_dwordx4 %[r6], %[pa], off offset:384\n\t"
-                        "global_load_dwordx4 %[r7], %[pa], off offset:448\n\t"
-                        "global_load_dwordx4 %[c0], %[pb], off\n\t"
-                        "s_waitcnt vmcnt(0)"
-                        : [r0] "=&v"(ra[0]),
-                          [r1] "=&v"(ra[1]),
-                          [r2] "=&v"(ra[2]),
-                          [r3] "=&v"(ra[3]),
-                          [r4] "=&v"(ra[4]),
-                          [r5] "=&v"(ra[5]),
-                          [r6] "=&v"(ra[6]),
-                          [r7] "=&v"(ra[7]),
-                          [c0] "=&v"(cb)
-                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
-                }
-                if constexpr (!F8 && !A_PC && !B_PC) {
-                    asm volatile("global_load_dword %[r0], %[pa], off\n\t"
-                        "global_load_dword %[c0], %[pb], off\n\t"
-                        "s_waitcnt vmcnt(0)"
-                        : [r0] "=&v"(ra_s),
-                          [c0] "=&v"(cb_s)
-                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
-                }
-                if constexpr (!F8 && !A_PC && B_PC) {
-                    asm volatile("global_load_dword %[r0], %[pa], off\n\t"
-                        "global_load_dwordx2 %[c0], %[pb], off\n\t"
-                        "s_waitcnt vmcnt(0)"
-                        : [r0] "=&v"(ra_s),
-                          [c0] "=&v"(cb)
-                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
-                }
-                if constexpr (!F8 && A_PC && !B_PC) {
-                    asm volatile("global_load_dwordx4 %[r0], %[pa], off\n\t"
-                        "global_load_dwordx4 %[r1], %[pa], off offset:32\n\t"
-                        "global_load_dwordx4 %[r2], %[pa], off offset:64\n\t"
-                        "global_load_dwordx4 %[r3], %[pa], off offset:96\n\t"
-                        "global_load_dwordx4 %[r4], %[pa], off offset:128\n\t"
-                        "global_load_dwordx4 %[r5], %[pa], off offset:160\n\t"
-                        "global_load_dwordx4 %[r6], %[pa], off offset:192\n\t"
-                        "global_load_dwordx4 %[r7], %[pa], off offset:224\n\t"
-                        "global_load_dwordx4 %[r8], %[pa], off offset:256\n\t"
-                        "global_load_dwordx4 %[r9], %[pa], off offset:288\n\t"
-                        "global_load_dwordx4 %[r10], %[pa], off offset:320\n\t"
-                        "global_load_dwordx4 %[r11], %[pa], off offset:352\n\t"
-                        "global_load_dwordx4 %[r12], %[pa], off offset:384\n\t"
-                        "global_load_dwordx4 %[r13], %[pa], off offset:416\n\t"
-                        "global_load_dwordx4 %[r14], %[pa], off offset:448\n\t"
-                        "global_load_dwordx4 %[r15], %[pa], off offset:480\n\t"
-                        "global_load_dword %[c0], %[pb], off\n\t"
-                        "s_waitcnt vmcnt(0)"
-                        : [r0] "=&v"(ra[0]),
-                          [r1] "=&v"(ra[1]),
-                          [r2] "=&v"(ra[2]),
-                          [r3] "=&v"(ra[3]),
-                          [r4] "=&v"(ra[4]),
-                          [r5] "=&v"(ra[5]),
-                          [r6] "=&v"(ra[6]),
-                          [r7] "=&v"(ra[7]),
-                          [r8] "=&v"(ra[8]),
-                          [r9] "=&v"(ra[9]),
-                          [r10] "=&v"(ra[10]),
-                          [r11] "=&v"(ra[11]),
-                          [r12] "=&v"(ra[12]),
-                          [r13] "=&v"(ra[13]),
-                          [r14] "=&v"(ra[14]),
-                          [r15] "=&v"(ra[15]),
-                          [c0] "=&v"(cb_s)
-                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
-                }
-                if constexpr (!F8 && A_PC && B_PC) {
-                    asm volatile("global_load_dwordx4 %[r0], %[pa], off\n\t"
-                        "global_load_dwordx4 %[r1], %[pa], off offset:32\n\t"
-                        "global_load_dwordx4 %[r2], %[pa], off offset:64\n\t"
-                        "global_load_dwordx4 %[r3], %[pa], off offset:96\n\t"
-                        "global_load_dwordx4 %[r4], %[pa], off offset:128\n\t"
-                        "global_load_dwordx4 %[r5], %[pa], off offset:160\n\t"
-                        "global_load_dwordx4 %[r6], %[pa], off offset:192\n\t"
-                        "global_load_dwordx4 %[r7], %[pa], off offset:224\n\t"
-                        "global_load_dwordx4 %[r8], %[pa], off offset:256\n\t"
-                        "global_load_dwordx4 %[r9], %[pa], off offset:288\n\t"
-                        "global_load_dwordx4 %[r10], %[pa], off offset:320\n\t"
-                        "global_load_dwordx4 %[r11], %[pa], off offset:352\n\t"
-                        "global_load_dwordx4 %[r12], %[pa], off offset:384\n\t"
-                        "global_load_dwordx4 %[r13], %[pa], off offset:416\n\t"
-                        "global_load_dwordx4 %[r14], %[pa], off offset:448\n\t"
-                        "global_load_dwordx4 %[r15], %[pa], off offset:480\n\t"
-                        "global_load_dwordx2 %[c0], %[pb], off\n\t"
-                        "s_waitcnt vmcnt(0)"
-                        : [r0] "=&v"(ra[0]),
-                          [r1] "=&v"(ra[1]),
-                          [r2] "=&v"(ra[2]),
-                          [r3] "=&v"(ra[3]),
-                          [r4] "=&v"(ra[4]),
-                          [r5] "=&v"(ra[5]),
-                          [r6] "=&v"(ra[6]),
-                          [r7] "=&v"(ra[7]),
-                          [r8] "=&v"(ra[8]),
-                          [r9] "=&v"(ra[9]),
-                          [r10] "=&v"(ra[10]),
-                          [r11] "=&v"(ra[11]),
-                          [r12] "=&v"(ra[12]),
-                          [r13] "=&v"(ra[13]),
-                          [r14] "=&v"(ra[14]),
-                          [r15] "=&v"(ra[15]),
-                          [c0] "=&v"(cb)
-                        : [pa] "v"(pa), [pb] "v"(pb) : "memory");
-                }
-#endif
                 before_stores();
                 store_tile([&](int ia, int r, int tt) -> float {
                     float sl, sr;
-                    if constexpr (A_PC) sl = F8 ? ra[ia][r] : ra[ia * 4 + (r >> 2)][r & 3]; else sl = ra_s;
-                    if constexpr (B_PC) sr = cb[tt]; else sr = cb_s;
+                    if constexpr (A_PC) {
+                        const int row = ia * R + row_in_block(r);                  // 0 .. 127, rows < 64 for the first half of the blocks
+                        const int got = __builtin_amdgcn_ds_bpermute((row & 63) * 4, __builtin_bit_cast(int, ia * R < 64 ? sc_a0 : sc_a1));
+                        sl = __builtin_bit_cast(float, got);
+                    } else sl = sc_a0;
+                    if constexpr (B_PC) sr = tt == 0 ? sc_b0 : tt == 1 ? sc_b1 : tt == 2 ? sc_b2 : sc_b3; else sr = sc_b0;
                     return (accumulator(ia, r, tt) * sl) * sr;
                 });
             };
@@ -1860,16 +1744,19 @@ splitk_reduce(GemmArgs g)
     }
 }
 
-// Split-K plan: used when even 128 x 128 tiles would leave CUs idle and K is long (weight-gradient
-// shapes: small output, contraction over all tokens).  Returns the number of K ranges (1 = no split).
+// Split-K plan: used when 128 x 128 tiles would not give every CU its two workgroups and K is long (weight-gradient
+// shapes: small output, contraction over all tokens).  Returns the number of K ranges (1 = no split).  The ranges run
+// as workgroups of the 128 x 128 kernel, about 512 of them (two per CU): measured on 1024 x 1024 x 16384 that takes
+// 29 us where sixteen ranges of 256 x 256 tiles took 37 (half as many partial sums for the second pass to add), and on
+// 3072 x 1024 x 16384 two ranges take 60 us where the unsplit product took 65; from 256 small tiles on (4096 x 1024)
+// the second pass costs more than the idle halves of the CUs.
 int plan_splits(int64_t M, int64_t N, int64_t rowbytes, int64_t batch, int fuse)
 {
     if (fuse != 0) return 1;
-    const int64_t big = ((M + 255) / 256) * ((N + 255) / 256) * batch;
     const int64_t small = ((M + 127) / 128) * ((N + 127) / 128) * batch;
     const int64_t nslabs = (rowbytes + kSlabBytes - 1) / kSlabBytes;
-    if (small >= 192 || nslabs < 16) return 1;       // 128 x 128 tiles fill the chip: cheaper than a second pass
-    int64_t splits = 256 / big;
+    if (small >= 256 || nslabs < 16) return 1;
+    int64_t splits = 512 / small;
     if (splits > nslabs / 8) splits = nslabs / 8;      // at least eight slabs per range
     return splits >= 2 ? (int)splits : 1;
 }
@@ -1981,6 +1868,7 @@ qmm_status launch_stream(GemmArgs& g, hipStream_t s)
     g.tiles_m = (int)(g.M / 256);
     g.tiles_n = (int)(g.N / 256);
     if ((int64_t)g.tiles_m * g.tiles_n * g.batch > 0x7FFFFFFF) return QMM_ERR_UNSUPPORTED;
+    g.stagger = ((int64_t)g.tiles_m * g.tiles_n * g.batch >= 4 * kStreamGrid) ? 16 : 0;
     auto kern = gemm_stream_kernel<KIND, FA, FB>;
     static std::atomic<uint64_t> lds_attr_done{0};
     if (!ensure_lds_attr(lds_attr_done, reinterpret_cast<const void*>(kern), LDS_BYTES)) return QMM_ERR_LAUNCH;
@@ -2010,7 +1898,7 @@ qmm_status launch_fuse(GemmArgs& g, hipStream_t s)
     const int64_t big = ((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
     // an output narrower than half a big tile wastes less of a small one
     const bool narrow = g.M <= 128 || g.N <= 128;
-    if ((big >= 192 && !narrow) || g.splits > 1) return launch_tile<KIND, FA, FB, 4, 1, 4, FUSE>(g, s);
+    if (big >= 192 && !narrow && g.splits == 1) return launch_tile<KIND, FA, FB, 4, 1, 4, FUSE>(g, s);
     return launch_tile<KIND, FA, FB, 2, 1, 2, FUSE>(g, s);
 }
 
