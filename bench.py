@@ -236,11 +236,12 @@ def main():
     def mfma_only(codes, f=None):
         f = fmt if f is None else f
         ts = []
-        for _ in range(4):       # about 1 ms each, so that dispatch latency does not count
+        for it in range(16):     # about 1 ms each, so that dispatch latency does not count; the first ten let the clock settle
             e0, e1 = event_pair()
             e0.record(); _, fl = qmm.mfma_rate(codes, f, f, rounds=1000, workgroups=n_cu, sink=sink); e1.record()
-            torch.cuda.synchronize(); ts.append(e0.elapsed_time(e1))
-        return fl / (sorted(ts[1:])[1] * 1e-3) / 1e12
+            torch.cuda.synchronize()
+            if it >= 10: ts.append(e0.elapsed_time(e1))
+        return fl / (sorted(ts)[len(ts) // 2] * 1e-3) / 1e12
     big = max(state, key=lambda st: st["cx"].numel())
     const_code = 0x38 if fmt != qmm.INT8 else 0x40
     mfma_codes = mfma_only(big["cx"].view(-1))
