@@ -17,7 +17,7 @@ step in E4M3; the same line carries, measured after the timed region:
 Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_large_fwd|bert_base_fwd]
-                    [--format e4m3|e5m2|int8] [--no-cpu-baseline] [--no-extras] [--full]
+                    [--format e4m3|e5m2|int8] [--settle-ms T] [--no-cpu-baseline] [--no-extras] [--full]
 The line on stdout is compact (numbers per section); every table goes to gpurun_out/bench_detail.json.
 """
 import argparse
@@ -54,6 +54,8 @@ def main():
     ap.add_argument("--workload", default="bert_large_fwd", choices=["bert_large_fwd", "bert_base_fwd"])
     ap.add_argument("--format", default="e4m3", choices=["e4m3", "e5m2", "int8"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--settle-ms", type=float, default=15.0,
+                    help="run the step untimed for this long before the warm-up steps, so that the clock has settled (0: off)")
     ap.add_argument("--no-extras", action="store_true", help="only the timed step (what the profiling commands run)")
     ap.add_argument("--full", action="store_true", help="print every table in the line instead of the compact form")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -164,6 +166,14 @@ def main():
 
         # Timed region: whole steps, with a pair of HIP events around every launch of the dominant kernel only (an
         # event pair costs several us of stream time; around all 16 launches of a step it would add a tenth to it).
+        # Set-up, untimed: the step runs until the GPU has been busy for `--settle-ms` (the part's clock under this load
+        # takes some 10 ms to settle; a step is half a millisecond, so a handful of warm-up steps end while it still
+        # ramps and the steps timed behind them read 5 % low).  Then the W warm-up steps, then exactly K timed steps.
+        t_settle = time.perf_counter()
+        while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+            for _ in range(4):
+                step(())
+            torch.cuda.synchronize()
         for _ in range(warmup):
             step(())
         torch.cuda.synchronize()
@@ -204,7 +214,7 @@ def main():
            "dtype": DTYPE[args.format], "data": "synthetic",
            "config": {"workload": f"{args.workload} ({args.format}, per-tensor, bf16 out): scale+quantize+gemm+metric of QKV, "
                                   f"attn_out, FFN1, FFN2; tokens {dims['tokens']}, hidden {dims['hidden']}, ffn {dims['ffn']}",
-                      "flops_per_step": flops},
+                      "flops_per_step": flops, "settle_ms_before_warmup": args.settle_ms},
            "roofline": roofline, "passes": passes, "gemm_tflops": round(main_res["gemm_tflops"], 1), "nsr": main_res["nsr"]}
     if args.no_extras:
         out["cpu_baseline"] = None
