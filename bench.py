@@ -35,6 +35,7 @@ if ROOT not in sys.path:
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemm_traffic.json")
 PEAK = {"e4m3": 5000.0, "e5m2": 5000.0, "int8": 5000.0}   # dense MFMA TFLOP/s (TOP/s), MI355X
 HBM_PEAK_GBS = 8000.0
+GEMM_EVENT_EVERY = 4       # timed region: HIP events around the GEMM launches of every fourth step
 DTYPE = {"e4m3": "fp8_e4m3", "e5m2": "fp8_e5m2", "int8": "int8"}
 
 
@@ -164,8 +165,9 @@ def main():
                 timed("gemm", record, lambda: qmm.gemm((st["cx"], st["oa"]), (st["cw"], st["ob"]), out=st["y"]))
                 timed("metric", record, lambda: qmm.metric(st["y"], st["y_ref"], out=st["m"], workspace=st["ws"]))
 
-        # Timed region: whole steps, with a pair of HIP events around every launch of the dominant kernel only (an
-        # event pair costs several us of stream time; around all 16 launches of a step it would add a tenth to it).
+        # Timed region: whole steps, with a pair of HIP events around the launches of the dominant kernel only, in every
+        # fourth step (an event pair costs several us of stream time: around all 16 launches of every step it would add a
+        # tenth to the step, around the four GEMM launches of every step still 4 %).
         # Set-up, untimed: the step runs until the GPU has been busy for `--settle-ms` (the part's clock under this load
         # takes some 10 ms to settle; a step is half a millisecond, so a handful of warm-up steps end while it still
         # ramps and the steps timed behind them read 5 % low).  Then the W warm-up steps, then exactly K timed steps.
@@ -178,19 +180,20 @@ def main():
             step(())
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(steps):
-            step(("gemm",))
+        for i in range(steps):
+            step(("gemm",) if i % GEMM_EVENT_EVERY == 0 else ())
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         for _ in range(steps):
             step(("scale", "quantize", "metric"))
         torch.cuda.synchronize()
-        per_kind_ms = {k: sum(a.elapsed_time(b) for a, b in v) / steps for k, v in events.items()}
+        n_gemm_steps = (steps + GEMM_EVENT_EVERY - 1) // GEMM_EVENT_EVERY
+        per_kind_ms = {k: sum(a.elapsed_time(b) for a, b in v) / (n_gemm_steps if k == "gemm" else steps) for k, v in events.items()}
         g_ms = [a.elapsed_time(b) for a, b in events["gemm"]]       # launch order: step-major, op-minor
         gemm_tflops = flops / (per_kind_ms["gemm"] * 1e-3) / 1e12
         res = {"ms_per_step": dt / steps * 1e3, "value": flops / (dt / steps) / 1e12, "gemm_tflops": gemm_tflops,
                "gemm_ms_per_launch": per_kind_ms["gemm"] / len(ops), "per_kind_ms": per_kind_ms,
-               "median_launch_ms_by_op": {st["op"].name: round(sorted(g_ms[i::len(ops)])[steps // 2], 4)
+               "median_launch_ms_by_op": {st["op"].name: round(sorted(g_ms[i::len(ops)])[n_gemm_steps // 2], 4)
                                           for i, st in enumerate(state)},
                "nsr": {st["op"].name: float(st["m"][0].item() / st["m"][1].item()) for st in state}}
         res["passes"] = {k: {"ms_per_step": round(per_kind_ms[k], 4),
