@@ -18,7 +18,7 @@ Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_large_fwd|bert_base_fwd]
                     [--format e4m3|e5m2|int8] [--settle-ms T] [--no-cpu-baseline] [--no-extras] [--full]
-The line on stdout is compact (numbers per section); every table goes to gpurun_out/bench_detail.json.
+The line on stdout is compact (numbers per section); every table goes to a JSON file whose path the line gives as `detail`.
 """
 import argparse
 import json
